@@ -1,0 +1,319 @@
+// C ABI of libzp (see include/zp.h): argument checks, LDS layout, kernel dispatch, the
+// host-side block planner and the slow full validator.  No torch types, no hidden allocation
+// after zp_create.
+#include "../../include/zp.h"
+#include "zp_kernels.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <unordered_set>
+#include <vector>
+
+struct zp_ctx {
+    int device;
+    int *d_status;   // 4 words on the device
+    int *h_status;   // pinned mirror
+    char err[512];
+};
+
+static thread_local char g_err[512] = "";
+
+static zp_status fail(zp_ctx *ctx, zp_status code, const char *fmt, ...) {
+    char *dst = ctx ? ctx->err : g_err;
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(dst, 512, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+extern "C" const char *zp_last_error(const zp_ctx *ctx) { return ctx ? ctx->err : g_err; }
+
+extern "C" zp_status zp_create(zp_ctx **out) {
+    if (!out) return fail(nullptr, ZP_EINVAL, "zp_create: out is NULL");
+    *out = nullptr;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(nullptr, ZP_EHIP, "zp_create: no HIP device (%s)", hipGetErrorString(e));
+    zp_ctx *c = new (std::nothrow) zp_ctx();
+    if (!c) return fail(nullptr, ZP_ENOMEM, "zp_create: out of host memory");
+    c->device = dev;
+    c->err[0] = 0;
+    if ((e = hipMalloc((void **)&c->d_status, 4 * sizeof(int))) != hipSuccess ||
+        (e = hipHostMalloc((void **)&c->h_status, 4 * sizeof(int), hipHostMallocDefault)) != hipSuccess ||
+        (e = hipMemset(c->d_status, 0, 4 * sizeof(int))) != hipSuccess) {
+        zp_status rc = fail(nullptr, ZP_EHIP, "zp_create: %s", hipGetErrorString(e));
+        if (c->d_status) (void)hipFree(c->d_status);
+        delete c;
+        return rc;
+    }
+    *out = c;
+    return ZP_OK;
+}
+
+extern "C" void zp_destroy(zp_ctx *ctx) {
+    if (!ctx) return;
+    (void)hipFree(ctx->d_status);
+    (void)hipHostFree(ctx->h_status);
+    delete ctx;
+}
+
+extern "C" size_t zp_scratch_bytes(const zp_pool *, const zp_batch *) { return 4 * sizeof(int); }
+
+static int align16(int x) { return (x + 15) & ~15; }
+static const int kLdsLimit = 160 * 1024;
+
+enum Path { PATH_GENERIC, PATH_MFMA };
+
+// Scalar checks shared by every call, and the kernel argument block.  `need_q`: the call scores.
+static zp_status prepare(zp_ctx *ctx, const char *who, const zp_pool *p, const zp_batch *b, bool need_q, zp::Args *a,
+                         Path *path, int *NW, int *RB) {
+    if (!ctx) return fail(nullptr, ZP_EINVAL, "%s: ctx is NULL", who);
+    if (!p || !b) return fail(ctx, ZP_EINVAL, "%s: pool or batch is NULL", who);
+    if (p->dtype != ZP_F32 && p->dtype != ZP_BF16) return fail(ctx, ZP_EINVAL, "%s: unknown dtype %d", who, p->dtype);
+    if (p->L_slab <= 0 || p->layer0 < 0 || p->N_total <= 0 || p->b <= 0 || p->h_kv <= 0 || p->h_q <= 0 || p->d <= 0 ||
+        p->M <= 0 || p->w <= 0)
+        return fail(ctx, ZP_EINVAL, "%s: pool dimensions must be positive", who);
+    if (b->B < 0 || b->N_max < 2 || b->max_blocks < b->N_max || b->L < p->layer0 + p->L_slab)
+        return fail(ctx, ZP_EINVAL, "%s: need B >= 0, N_max >= 2, max_blocks >= N_max, L >= layer0 + L_slab", who);
+    if (!p->k || !p->v) return fail(ctx, ZP_EINVAL, "%s: k / v pool pointer is NULL", who);
+    if (b->B > 0 && (!b->block_table || !b->num_blocks)) return fail(ctx, ZP_EINVAL, "%s: block_table / num_blocks is NULL", who);
+    if (need_q && (!p->q || (b->B > 0 && !b->q_slot))) return fail(ctx, ZP_EINVAL, "%s: q / q_slot is NULL", who);
+    if (p->h_q % p->h_kv) return fail(ctx, ZP_EUNSUPPORTED, "%s: h_q %d is not a multiple of h_kv %d", who, p->h_q, p->h_kv);
+    const int esz = p->dtype == ZP_F32 ? 4 : 2;
+    const long long row_bytes = (long long)p->d * esz;
+    if (row_bytes % 16 || row_bytes > 1024) return fail(ctx, ZP_EUNSUPPORTED, "%s: row of %lld bytes (need a multiple of 16, at most 1024)", who, row_bytes);
+    const long long T_max = (long long)b->max_blocks * p->b, budget = (long long)(b->N_max - 1) * p->b;
+    if (budget < p->w) return fail(ctx, ZP_EINVAL, "%s: budget %lld smaller than the window %d", who, budget, p->w);
+    if (T_max > 65535) return fail(ctx, ZP_EUNSUPPORTED, "%s: %lld positions per request exceed 65535", who, T_max);
+    const long long units = (long long)b->B * p->L_slab * p->h_kv;
+    if (units > 0x7fffffffLL) return fail(ctx, ZP_EUNSUPPORTED, "%s: too many units", who);
+
+    memset(a, 0, sizeof(*a));
+    a->k = (char *)p->k; a->v = (char *)p->v; a->q = (const char *)p->q;
+    a->layer0 = p->layer0; a->L_slab = p->L_slab; a->N_total = p->N_total; a->b = p->b; a->h_kv = p->h_kv; a->h_q = p->h_q;
+    a->d = p->d; a->M = p->M; a->w = p->w; a->dtype = p->dtype;
+    a->B = b->B; a->N_max = b->N_max; a->max_blocks = b->max_blocks; a->L = b->L;
+    a->block_table = b->block_table; a->dst_table = b->dst_table; a->num_blocks = b->num_blocks; a->q_slot = b->q_slot;
+    a->valid_len = b->valid_len; a->keep = b->keep;
+    a->G = p->h_q / p->h_kv; a->T_max = (int)T_max; a->budget = (int)budget; a->row_bytes = (int)row_bytes;
+    a->b_shift = -1;
+    for (int s = 0; s < 31; s++) if ((1 << s) == p->b) a->b_shift = s;
+    a->scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)p->d));
+    a->status = ctx->d_status;
+
+    *path = PATH_GENERIC;
+    *NW = 4; *RB = 0;
+    size_t score_bytes = (size_t)a->G * a->w * 4;
+    if (need_q && zp::mfma_path_available(*a, NW, RB)) {
+        *path = PATH_MFMA;
+        const int UL = 16 / a->G;
+        a->NB = (a->w + 2 * UL - 1) / (2 * UL);
+        score_bytes = zp::mfma_union_bytes(a->d, *NW, *NW * *RB);
+    }
+    if (!need_q) score_bytes = 0;
+    const size_t list_bytes = (size_t)a->budget * 4;
+    a->off_S = 0;
+    a->off_tbl = align16(a->T_max * 4);
+    a->off_dst = a->off_tbl + align16(a->max_blocks * 4);
+    a->off_misc = a->off_dst + align16((a->N_max - 1) * 4);
+    a->off_union = a->off_misc + align16((int)sizeof(int) * (256 + 16 + 4));
+    const size_t total = (size_t)a->off_union + (score_bytes > list_bytes ? score_bytes : list_bytes);
+    if (total > (size_t)kLdsLimit)
+        return fail(ctx, ZP_EUNSUPPORTED, "%s: %zu bytes of LDS per unit exceed %d (max_blocks*b too large)", who, total, kLdsLimit);
+    a->lds_bytes = (int)align16((int)total);
+    return ZP_OK;
+}
+
+static zp_status launch(zp_ctx *ctx, const char *who, const zp::Args &a, Path path, int NW, int RB, void *stream) {
+    const int units = a.B * a.L_slab * a.h_kv;
+    hipError_t e = path == PATH_MFMA ? zp::launch_unit_mfma(a, units, NW, RB, (hipStream_t)stream)
+                                     : zp::launch_unit_generic(a, units, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(ctx, ZP_EHIP, "%s: kernel launch failed: %s", who, hipGetErrorString(e));
+    return ZP_OK;
+}
+
+extern "C" zp_status zp_score(zp_ctx *ctx, const zp_pool *pool, const zp_batch *batch, float *scores, void *stream) {
+    zp::Args a; Path path; int NW, RB;
+    zp_status rc = prepare(ctx, "zp_score", pool, batch, true, &a, &path, &NW, &RB);
+    if (rc) return rc;
+    if (!scores && batch->B > 0) return fail(ctx, ZP_EINVAL, "zp_score: scores is NULL");
+    a.stages = zp::STAGE_SCORE;
+    a.scores_out = scores;
+    return launch(ctx, "zp_score", a, path, NW, RB, stream);
+}
+
+extern "C" zp_status zp_select_topk(zp_ctx *ctx, const float *scores, int32_t T_max, const zp_pool *pool, const zp_batch *batch,
+                                    int32_t *keep_idx, int32_t *len_out, void *stream) {
+    zp::Args a; Path path; int NW, RB;
+    zp_status rc = prepare(ctx, "zp_select_topk", pool, batch, false, &a, &path, &NW, &RB);
+    if (rc) return rc;
+    if ((!scores || !keep_idx || !len_out) && batch->B > 0) return fail(ctx, ZP_EINVAL, "zp_select_topk: scores / keep_idx / len_out is NULL");
+    if (T_max < a.T_max) return fail(ctx, ZP_EINVAL, "zp_select_topk: T_max %d smaller than max_blocks*b = %d", T_max, a.T_max);
+    a.stages = zp::STAGE_LOAD_SCORES | zp::STAGE_SELECT;
+    a.scores_in = scores; a.scores_in_stride = T_max;
+    a.keep_idx_out = keep_idx; a.len_out = len_out;
+    return launch(ctx, "zp_select_topk", a, PATH_GENERIC, NW, RB, stream);
+}
+
+extern "C" zp_status zp_compact_kv(zp_ctx *ctx, const zp_pool *pool, const zp_batch *batch, const int32_t *keep_idx,
+                                   const int32_t *len, void *stream) {
+    zp::Args a; Path path; int NW, RB;
+    zp_status rc = prepare(ctx, "zp_compact_kv", pool, batch, false, &a, &path, &NW, &RB);
+    if (rc) return rc;
+    if ((!keep_idx || !len) && batch->B > 0) return fail(ctx, ZP_EINVAL, "zp_compact_kv: keep_idx / len is NULL");
+    a.stages = zp::STAGE_LOAD_LIST | zp::STAGE_COMPACT;
+    a.keep_idx_in = keep_idx; a.len_in = len;
+    return launch(ctx, "zp_compact_kv", a, PATH_GENERIC, NW, RB, stream);
+}
+
+extern "C" zp_status zp_compress(zp_ctx *ctx, const zp_pool *pool, const zp_batch *batch, int32_t *len_out, float *scores_dbg,
+                                 int32_t *keep_idx_dbg, void *stream) {
+    zp::Args a; Path path; int NW, RB;
+    zp_status rc = prepare(ctx, "zp_compress", pool, batch, true, &a, &path, &NW, &RB);
+    if (rc) return rc;
+    if (!len_out && batch->B > 0) return fail(ctx, ZP_EINVAL, "zp_compress: len_out is NULL");
+    a.stages = zp::STAGE_SCORE | zp::STAGE_SELECT | zp::STAGE_COMPACT;
+    a.scores_out = scores_dbg; a.keep_idx_out = keep_idx_dbg; a.len_out = len_out;
+    return launch(ctx, "zp_compress", a, path, NW, RB, stream);
+}
+
+extern "C" zp_status zp_sync_status(zp_ctx *ctx, void *stream) {
+    if (!ctx) return fail(nullptr, ZP_EINVAL, "zp_sync_status: ctx is NULL");
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = hipMemcpyAsync(ctx->h_status, ctx->d_status, 4 * sizeof(int), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return fail(ctx, ZP_EHIP, "zp_sync_status: %s", hipGetErrorString(e));
+    if (!ctx->h_status[0]) return ZP_OK;
+    const int unit = ctx->h_status[1], reason = ctx->h_status[2];
+    e = hipMemsetAsync(ctx->d_status, 0, 4 * sizeof(int), s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    static const char *names[] = {"?", "num_blocks outside [N_max, max_blocks]", "valid_len out of range", "keep count out of range",
+                                  "query slot out of range", "block id out of range", "keep_idx not ascending or out of range"};
+    return fail(ctx, ZP_EINVAL, "a kernel skipped unit %d: %s", unit, reason >= 1 && reason <= 6 ? names[reason] : names[0]);
+}
+
+extern "C" zp_status zp_validate_batch(zp_ctx *ctx, const zp_pool *p, const zp_batch *b) {
+    zp::Args a; Path path; int NW, RB;
+    zp_status rc = prepare(ctx, "zp_validate_batch", p, b, true, &a, &path, &NW, &RB);
+    if (rc) return rc;
+    const int B = b->B, nt = b->N_max - 1;
+    const size_t per = (size_t)b->L * p->h_kv;
+    std::vector<int> tbl((size_t)B * b->max_blocks), dst, nb(B), slot(B), vl, keep;
+    hipError_t e = hipDeviceSynchronize();
+    auto pull = [&](std::vector<int> &h, const int *d, size_t n) {
+        h.resize(n);
+        if (e == hipSuccess && n) e = hipMemcpy(h.data(), d, n * sizeof(int), hipMemcpyDeviceToHost);
+    };
+    pull(tbl, b->block_table, tbl.size());
+    pull(nb, b->num_blocks, B);
+    pull(slot, b->q_slot, B);
+    if (b->dst_table) pull(dst, b->dst_table, (size_t)B * nt);
+    if (b->valid_len) pull(vl, b->valid_len, B * per);
+    if (b->keep) pull(keep, b->keep, B * per);
+    if (e != hipSuccess) return fail(ctx, ZP_EHIP, "zp_validate_batch: %s", hipGetErrorString(e));
+    std::unordered_set<int> sources, targets_seen, slots_seen;
+    for (int n = 0; n < B; n++)
+        for (int i = 0; i < nb[n] && i < b->max_blocks; i++) sources.insert(tbl[(size_t)n * b->max_blocks + i]);
+    for (int n = 0; n < B; n++) {
+        const int N = nb[n];
+        if (N < b->N_max || N > b->max_blocks) return fail(ctx, ZP_EINVAL, "request %d: num_blocks %d outside [%d, %d]", n, N, b->N_max, b->max_blocks);
+        if (slot[n] < 0 || slot[n] >= p->M) return fail(ctx, ZP_EINVAL, "request %d: query slot %d outside [0, %d)", n, slot[n], p->M);
+        if (!slots_seen.insert(slot[n]).second) return fail(ctx, ZP_EINVAL, "request %d: query slot %d used twice", n, slot[n]);
+        std::unordered_set<int> own;
+        for (int i = 0; i < N; i++) {
+            const int id = tbl[(size_t)n * b->max_blocks + i];
+            if (id < 0 || id >= p->N_total) return fail(ctx, ZP_EINVAL, "request %d: block_table[%d] = %d outside the pool", n, i, id);
+            if (!own.insert(id).second) return fail(ctx, ZP_EINVAL, "request %d: block %d appears twice in its table", n, id);
+        }
+        for (int i = 0; i < nt; i++) {
+            const int src = tbl[(size_t)n * b->max_blocks + i];
+            const int id = b->dst_table ? dst[(size_t)n * nt + i] : src;
+            if (id < 0 || id >= p->N_total) return fail(ctx, ZP_EINVAL, "request %d: dst_table[%d] = %d outside the pool", n, i, id);
+            if (id != src && sources.count(id)) return fail(ctx, ZP_EINVAL, "request %d: dst_table[%d] = %d is a source block of the batch but not its own block %d", n, i, id, src);
+            if (!targets_seen.insert(id).second) return fail(ctx, ZP_EINVAL, "request %d: target block %d is written by two requests or twice", n, id);
+        }
+        for (int l = p->layer0; l < p->layer0 + p->L_slab; l++)
+            for (int h = 0; h < p->h_kv; h++) {
+                const size_t idx = (size_t)n * per + (size_t)l * p->h_kv + h;
+                const int v = b->valid_len ? vl[idx] : (N - 1) * p->b;
+                if (v < 0 || v > (N - 1) * p->b || v + p->b < p->w) return fail(ctx, ZP_EINVAL, "request %d layer %d head %d: valid_len %d out of range", n, l, h, v);
+                const int k = b->keep ? keep[idx] : a.budget;
+                const int cap = a.budget < v + p->b ? a.budget : v + p->b;
+                if (k < p->w || k > cap) return fail(ctx, ZP_EINVAL, "request %d layer %d head %d: keep %d outside [%d, %d]", n, l, h, k, p->w, cap);
+            }
+    }
+    return ZP_OK;
+}
+
+// ------------------------------------------------------------------ host planner
+extern "C" zp_status zp_plan(int32_t B, int32_t N_max, int32_t max_blocks, int32_t N_total, const int32_t *block_table,
+                             const int32_t *num_blocks, int32_t *refcnt, const int32_t *free_in, int32_t n_free_in,
+                             int32_t *n_free_used, int32_t *dst_table, int32_t *new_table, int32_t *freed, int32_t *n_freed) {
+    if (B < 0 || N_max < 2 || max_blocks < N_max || N_total <= 0) return fail(nullptr, ZP_EINVAL, "zp_plan: bad scalar argument");
+    if (!block_table || !num_blocks || !refcnt || !n_free_used || !dst_table || !new_table || !freed || !n_freed || (n_free_in > 0 && !free_in))
+        return fail(nullptr, ZP_EINVAL, "zp_plan: NULL argument");
+    const int nt = N_max - 1;
+    // pass 1: validate, and decide every target from the counts as they stand at entry
+    std::vector<int32_t> targets((size_t)B * nt), reserved(B);
+    std::vector<char> is_fresh((size_t)N_total, 0);
+    std::vector<int32_t> uses((size_t)N_total, 0);
+    int taken = 0;
+    for (int n = 0; n < B; n++) {
+        const int32_t *row = block_table + (size_t)n * max_blocks;
+        const int N = num_blocks[n];
+        if (N < N_max || N > max_blocks) return fail(nullptr, ZP_EINVAL, "zp_plan: request %d holds %d blocks, outside [%d, %d]", n, N, N_max, max_blocks);
+        for (int i = 0; i < N; i++)
+            if (row[i] < 0 || row[i] >= N_total || refcnt[row[i]] < 1)
+                return fail(nullptr, ZP_EINVAL, "zp_plan: request %d block_table[%d] = %d is outside the pool or unreferenced", n, i, row[i]);
+        for (int i = 0; i < N; i++)
+            if (++uses[row[i]] > refcnt[row[i]])
+                return fail(nullptr, ZP_EINVAL, "zp_plan: block %d is listed more often than its reference count", row[i]);
+        for (int i = 0; i < nt; i++) {
+            if (refcnt[row[i]] == 1) { targets[(size_t)n * nt + i] = row[i]; continue; }
+            if (taken == n_free_in) return fail(nullptr, ZP_ENOMEM, "zp_plan: free list of %d blocks exhausted at request %d", n_free_in, n);
+            const int f = free_in[taken++];
+            if (f < 0 || f >= N_total || refcnt[f] != 0 || is_fresh[f]) return fail(nullptr, ZP_EINVAL, "zp_plan: free_in entry %d is not a free block", f);
+            is_fresh[f] = 1;
+            targets[(size_t)n * nt + i] = f;
+        }
+        int r = nt;
+        while (r < N && refcnt[row[r]] != 1) r++;
+        if (r == N) return fail(nullptr, ZP_EINVAL, "zp_plan: request %d has no private block at index >= %d to reserve", n, nt);
+        reserved[n] = r;
+    }
+    // pass 2: commit
+    std::vector<char> was_shared((size_t)N_total, 0);
+    for (int n = 0; n < B; n++) {
+        const int32_t *row = block_table + (size_t)n * max_blocks;
+        for (int i = 0; i < num_blocks[n]; i++)
+            if (refcnt[row[i]] > 1) was_shared[row[i]] = 1;
+    }
+    int nf = 0;
+    for (int n = 0; n < B; n++) {
+        const int32_t *row = block_table + (size_t)n * max_blocks;
+        const int N = num_blocks[n];
+        for (int i = 0; i < nt; i++) {
+            const int32_t t = targets[(size_t)n * nt + i];
+            dst_table[(size_t)n * nt + i] = t;
+            new_table[(size_t)n * N_max + i] = t;
+            if (is_fresh[t]) refcnt[t] = 1;
+        }
+        new_table[(size_t)n * N_max + nt] = row[reserved[n]];
+        for (int i = 0; i < N; i++) {
+            const int32_t p = row[i];
+            if (was_shared[p]) {
+                if (--refcnt[p] == 0) freed[nf++] = p;
+            } else if (i >= nt && i != reserved[n]) {
+                refcnt[p] = 0;
+                freed[nf++] = p;
+            }
+        }
+    }
+    *n_free_used = taken;
+    *n_freed = nf;
+    return ZP_OK;
+}

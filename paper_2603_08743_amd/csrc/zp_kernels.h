@@ -1,0 +1,54 @@
+// Kernel-side argument block and launch entry points shared by the HIP sources of libzp.
+// Paper sections are cited as in include/zp.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace zp {
+
+enum : int {
+    STAGE_SCORE = 1,    // compute S from K and the window queries
+    STAGE_SELECT = 2,   // fill, top-k_h, ascending list
+    STAGE_COMPACT = 4,  // move kept K/V rows
+    STAGE_LOAD_SCORES = 8,  // S comes from args.scores_in instead of STAGE_SCORE
+    STAGE_LOAD_LIST = 16,   // the kept list comes from args.keep_idx_in / len_in
+};
+
+// Reasons a kernel skips a unit (reported through the context's status words).
+enum : int {
+    BAD_NUM_BLOCKS = 1, BAD_VALID_LEN = 2, BAD_KEEP = 3, BAD_SLOT = 4, BAD_BLOCK_ID = 5, BAD_KEEP_IDX = 6,
+};
+
+struct Args {
+    // paged memory (Background, "Pre-allocated memory"; Method, query cache)
+    char *k, *v;
+    const char *q;
+    int layer0, L_slab, N_total, b, h_kv, h_q, d, M, w, dtype;
+    // batch
+    int B, N_max, max_blocks, L;
+    const int *block_table, *dst_table, *num_blocks, *q_slot, *valid_len, *keep;
+    // derived on the host
+    int G, T_max, budget, row_bytes, b_shift;   // b_shift >= 0 iff b is a power of two
+    float scale_log2;                          // log2(e) / sqrt(d)
+    int stages;
+    // staged inputs / outputs (device pointers, any may be null depending on stages)
+    const float *scores_in; int scores_in_stride;
+    float *scores_out;                         // [units][T_max]
+    const int *keep_idx_in; const int *len_in;
+    int *keep_idx_out;                         // [units][budget]
+    int *len_out;                              // [units]
+    int *status;                               // [4]: flag, first bad unit, reason, spare
+    // byte offsets into dynamic LDS
+    int off_S, off_tbl, off_dst, off_misc, off_union, lds_bytes;
+    // MFMA path geometry
+    int NB;                                    // 32-row query blocks in use
+};
+
+// launchers (host).  Each returns the hipError_t of the launch.
+hipError_t launch_unit_generic(const Args &a, int units, hipStream_t s);
+// returns hipErrorInvalidConfiguration when no MFMA instantiation covers (d, G, w)
+bool mfma_path_available(const Args &a, int *NW, int *RB);
+hipError_t launch_unit_mfma(const Args &a, int units, int NW, int RB, hipStream_t s);
+size_t mfma_union_bytes(int d, int NW, int NB);
+
+}  // namespace zp

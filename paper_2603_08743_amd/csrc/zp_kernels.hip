@@ -1,0 +1,400 @@
+// Unit kernels of libzp: one workgroup per (request, layer, kv head).
+//
+//  * unit_generic: scoring on the vector ALUs for any element type / group size / head
+//    dimension (fp32 pools, odd shapes), and the staged select-only / compact-only passes.
+//  * unit_mfma: bf16 pools.  The (G*w) x T logits are a dense contraction over d, so they run
+//    on the matrix cores (v_mfma_f32_32x32x16_bf16) from LDS-staged key tiles.
+//
+// Scores follow the appendix "Paged Attention Score": softmax over positions per window
+// query, max over the query heads of the group, mean over the window.  The max over heads
+// needs the final normaliser of every row, and the (G*w) x T logits do not fit on chip, so
+// the keys are swept twice: sweep 1 reduces each row to its log-sum-exp, sweep 2 recomputes
+// the logits and reduces them to S[t] = (1/w) sum_u max_g exp(a[g,u,t] - lse[g,u]).
+#include "zp_device.h"
+
+namespace zp {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+__device__ __forceinline__ float fexp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float flog2(float x) { return __builtin_amdgcn_logf(x); }
+
+// ------------------------------------------------------------------ generic path
+
+template <int DT> __device__ __forceinline__ float ld_elem(const char *p, int i);
+template <> __device__ __forceinline__ float ld_elem<0>(const char *p, int i) { return ((const float *)p)[i]; }
+template <> __device__ __forceinline__ float ld_elem<1>(const char *p, int i) {
+    return __uint_as_float((unsigned)((const unsigned short *)p)[i] << 16);
+}
+
+template <int DT> __device__ __forceinline__ float dot_row(const char *q, const char *k, int d) {
+    float acc = 0.f;
+    for (int c = 0; c < d; c++) acc = fmaf(ld_elem<DT>(q, c), ld_elem<DT>(k, c), acc);
+    return acc;
+}
+
+template <int DT>
+__device__ void score_generic(const Args &a, const Unit &u, char *smem, const int *tbl) {
+    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wv = tid >> 6, nw = nt >> 6;
+    float *S = (float *)(smem + a.off_S);
+    float *lse = (float *)(smem + a.off_union);
+    const int G = a.G, w = a.w, rows = G * w;
+    const size_t qbase = (((size_t)u.ls * a.M + u.slot) * w) * a.h_q;   // in rows of d elements
+    for (int t = tid; t < u.T; t += nt) S[t] = 0.f;
+    // sweep 1: log-sum-exp (base 2) of every window row over the keys it may see
+    for (int r = wv; r < rows; r += nw) {
+        const int g = r / w, uu = r - g * w;
+        const char *q = a.q + (qbase + (size_t)uu * a.h_q + u.h * G + g) * a.row_bytes;
+        const int jmax = u.Tv - w + uu;                               // causal: keys after the query are hidden
+        float m = -1e30f, l = 0.f;
+        for (int j = lane; j <= jmax; j += 64) {
+            const int t = live_to_pos(u, a, j), blk = div_b(a, t);
+            const float x = dot_row<DT>(q, a.k + row_off(a, u.ls, tbl[blk], t - blk * a.b, u.h), a.d) * a.scale_log2;
+            if (x > m) { l = l * fexp2(m - x) + 1.f; m = x; }
+            else l += fexp2(x - m);
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const float mo = __shfl_xor(m, off), lo = __shfl_xor(l, off);
+            const float mm = fmaxf(m, mo);
+            l = l * fexp2(m - mm) + lo * fexp2(mo - mm);
+            m = mm;
+        }
+        if (lane == 0) lse[r] = m + flog2(l);
+    }
+    __syncthreads();
+    // sweep 2: S[t] = (1/w) sum_u max_g exp2(x - lse)
+    for (int j = tid; j < u.Tv; j += nt) {
+        const int t = live_to_pos(u, a, j), blk = div_b(a, t);
+        const char *kr = a.k + row_off(a, u.ls, tbl[blk], t - blk * a.b, u.h);
+        float acc = 0.f;
+        for (int uu = 0; uu < w; uu++) {
+            if (j > u.Tv - w + uu) continue;
+            float mx = 0.f;
+            for (int g = 0; g < G; g++) {
+                const char *q = a.q + (qbase + (size_t)uu * a.h_q + u.h * G + g) * a.row_bytes;
+                const float x = dot_row<DT>(q, kr, a.d) * a.scale_log2;
+                mx = fmaxf(mx, fexp2(x - lse[g * w + uu]));
+            }
+            acc += mx;
+        }
+        S[t] = acc / (float)w;
+    }
+    __syncthreads();
+}
+
+template <int DT>
+__global__ void __launch_bounds__(256) unit_generic(const Args a) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    int *tbl = (int *)(smem + a.off_tbl), *dst = (int *)(smem + a.off_dst);
+    Misc *misc = (Misc *)(smem + a.off_misc);
+    Unit u;
+    if (!unit_setup(a, blockIdx.x, u, tbl, dst, misc)) return;
+    if (a.stages & STAGE_SCORE) score_generic<DT>(a, u, smem, tbl);
+    unit_tail(a, u, smem, tbl, dst, misc);
+}
+
+// A workgroup may use the whole 160 KB of LDS; the runtime wants to be told once per kernel.
+template <class K> static hipError_t allow_big_lds(K kernel) {
+    static hipError_t state = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    return state;
+}
+
+hipError_t launch_unit_generic(const Args &a, int units, hipStream_t s) {
+    if (units <= 0) return hipSuccess;
+    hipError_t e = a.dtype == 0 ? allow_big_lds(unit_generic<0>) : allow_big_lds(unit_generic<1>);
+    if (e != hipSuccess) return e;
+    if (a.dtype == 0) hipLaunchKernelGGL(unit_generic<0>, dim3(units), dim3(256), a.lds_bytes, s, a);
+    else hipLaunchKernelGGL(unit_generic<1>, dim3(units), dim3(256), a.lds_bytes, s, a);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ MFMA path (bf16)
+//
+// Query rows are laid out so that both reductions of sweep 2 stay inside a lane.  A 32x32 MFMA
+// tile gives lane L, register i the element (row 4*(L/32) + 8*(i/4) + i%4, column L%32).  With
+// the query block as the row operand, one half-wave (hf = L/32) owns 16 rows of the block per
+// key column; those 16 slots hold UL = 16/G window rows u with their G query heads side by side
+// (slot i = ul*G + g; left-over slots are zero rows).  Block gb, half hf, slot i therefore is
+// window row u = (gb*2 + hf)*UL + i/G, head g = i%G.  NW waves split the NB blocks (RB each) and
+// share every key tile through LDS.  In sweep 1 the operands swap, so a lane owns one query row
+// and 16 keys per tile and the running (max, sum) of a row never leaves its lane.
+
+constexpr int KT = 64;   // keys per LDS tile
+
+template <int D> struct KTile {
+    static constexpr int ROW = D * 2 + 16;        // padded row stride in bytes: conflict-free 16-byte fragment reads
+    static constexpr int BYTES = KT * ROW;
+    static constexpr int CPR = D * 2 / 16;        // 16-byte pieces per key row
+};
+
+size_t mfma_union_bytes(int d, int NW, int NB) {
+    const size_t tile = (size_t)KT * (d * 2 + 16);
+    return 2 * tile + 2 * (size_t)NW * KT * 4 + (size_t)NB * 32 * 4;
+}
+
+template <int D, int RB, int NW, int GT>
+__global__ void __launch_bounds__(NW * 64) unit_mfma(const Args a) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    int *tbl = (int *)(smem + a.off_tbl), *dst = (int *)(smem + a.off_dst);
+    Misc *misc = (Misc *)(smem + a.off_misc);
+    Unit u;
+    if (!unit_setup(a, blockIdx.x, u, tbl, dst, misc)) return;
+
+    using KTl = KTile<D>;
+    constexpr int NT = NW * 64, KK = D / 16, LPT = KT * KTl::CPR / NT;
+    static_assert(KT * KTl::CPR % NT == 0, "tile pieces must divide evenly among the threads");
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hf = lane >> 5;
+    const int G = GT ? GT : a.G, UL = 16 / G, w = a.w;
+    float *S = (float *)(smem + a.off_S);
+    char *kbuf = smem + a.off_union;
+    float *part = (float *)(kbuf + 2 * KTl::BYTES);          // [2][NW][KT] partial sums of sweep 2
+    float *lse = part + 2 * NW * KT;                         // [NB*32] per padded query row
+    const float c = a.scale_log2;
+
+    for (int t = tid; t < u.T; t += NT) S[t] = 0.f;          // stale positions stay 0
+
+    // query fragments: this lane supplies padded row l32 of each of its blocks, 8 elements per 16-wide k step
+    bf16x8 qf[RB][KK];
+    int u_col[RB];                                           // window row this lane owns in sweep 1 (-1: zero row)
+#pragma unroll
+    for (int rb = 0; rb < RB; rb++) {
+        const int gb = wv * RB + rb;
+        const int mh = (l32 >> 2) & 1, i = ((l32 >> 3) << 2) | (l32 & 3);
+        const int ul = i / G, g = i - ul * G, uu = (gb * 2 + mh) * UL + ul;
+        const bool ok = ul < UL && uu < w;
+        u_col[rb] = ok ? uu : -1;
+        const char *qp = a.q + ((((size_t)u.ls * a.M + u.slot) * w + (ok ? uu : 0)) * a.h_q + u.h * G + g) * (size_t)(D * 2) + hf * 16;
+#pragma unroll
+        for (int kk = 0; kk < KK; kk++) {
+            u32x4 raw = {0u, 0u, 0u, 0u};
+            if (ok) raw = *(const u32x4 *)(qp + kk * 32);
+            qf[rb][kk] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
+
+    const int ntiles = (u.Tv + KT - 1) / KT;
+    u32x4 stage[LPT];
+    auto gload = [&](int tile) {                              // key tile -> registers (rows past the end repeat the last key)
+#pragma unroll
+        for (int i = 0; i < LPT; i++) {
+            const int cidx = tid + i * NT, row = cidx / KTl::CPR, ch = cidx - row * KTl::CPR;
+            int j = tile * KT + row;
+            j = j < u.Tv ? j : u.Tv - 1;
+            const int t = live_to_pos(u, a, j), blk = div_b(a, t);
+            stage[i] = *(const u32x4 *)(a.k + row_off(a, u.ls, tbl[blk], t - blk * a.b, u.h) + ch * 16);
+        }
+    };
+    auto lstore = [&](char *buf) {
+#pragma unroll
+        for (int i = 0; i < LPT; i++) {
+            const int cidx = tid + i * NT, row = cidx / KTl::CPR, ch = cidx - row * KTl::CPR;
+            *(u32x4 *)(buf + row * KTl::ROW + ch * 16) = stage[i];
+        }
+    };
+
+    // ---------------- sweep 1: per query row, running max and sum of exp2 over the keys it may see
+    float rm[RB], rl[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; rb++) { rm[rb] = -1e30f; rl[rb] = 0.f; }
+    gload(0);
+    lstore(kbuf);
+    __syncthreads();
+#pragma unroll 1
+    for (int it = 0; it < ntiles; it++) {
+        const char *buf = kbuf + (it & 1) * KTl::BYTES;
+        if (it + 1 < ntiles) gload(it + 1);
+        const int j0 = it * KT;
+        const bool edge = j0 + KT > u.Tv - w;                 // tile reaches the window or the end: mask needed
+#pragma unroll
+        for (int sub = 0; sub < KT / 32; sub++) {
+            f32x16 acc[RB];
+#pragma unroll
+            for (int rb = 0; rb < RB; rb++)
+#pragma unroll
+                for (int i = 0; i < 16; i++) acc[rb][i] = 0.f;
+            const char *kp = buf + (sub * 32 + l32) * KTl::ROW + hf * 16;
+#pragma unroll
+            for (int kk = 0; kk < KK; kk++) {
+                const bf16x8 kf = *(const bf16x8 *)(kp + kk * 32);
+#pragma unroll
+                for (int rb = 0; rb < RB; rb++) acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rb][kk], acc[rb], 0, 0, 0);
+            }
+            // acc[rb][i]: key j0 + sub*32 + 4*hf + 8*(i/4) + i%4, query row = this lane's column
+#pragma unroll
+            for (int rb = 0; rb < RB; rb++) {
+                if (edge) {
+                    const int lim = u_col[rb] >= 0 ? u.Tv - w + u_col[rb] : u.Tv - 1;
+#pragma unroll
+                    for (int i = 0; i < 16; i++) {
+                        const int j = j0 + sub * 32 + 4 * hf + 8 * (i >> 2) + (i & 3);
+                        if (j > lim) acc[rb][i] = -INFINITY;
+                    }
+                }
+                float tm = acc[rb][0];
+#pragma unroll
+                for (int i = 1; i < 16; i++) tm = fmaxf(tm, acc[rb][i]);
+                const float mn = fmaxf(rm[rb], tm * c);
+                float sum = 0.f;
+#pragma unroll
+                for (int i = 0; i < 16; i++) sum += fexp2(fmaf(acc[rb][i], c, -mn));
+                rl[rb] = rl[rb] * fexp2(rm[rb] - mn) + sum;
+                rm[rb] = mn;
+            }
+        }
+        if (it + 1 < ntiles) lstore(kbuf + ((it + 1) & 1) * KTl::BYTES);
+        __syncthreads();
+    }
+#pragma unroll
+    for (int rb = 0; rb < RB; rb++) {                         // the two half-waves hold the same row, different keys
+        const float mo = __shfl_xor(rm[rb], 32), lo = __shfl_xor(rl[rb], 32);
+        const float mm = fmaxf(rm[rb], mo);
+        const float ll = rl[rb] * fexp2(rm[rb] - mm) + lo * fexp2(mo - mm);
+        if (hf == 0) lse[(wv * RB + rb) * 32 + l32] = u_col[rb] >= 0 ? mm + flog2(ll) : INFINITY;
+    }
+    __syncthreads();
+
+    // ---------------- sweep 2: S[t] = (1/w) sum_u max_g exp2(x - lse)
+    float lr[RB][16];
+    int ub[RB];                                               // first window row of this half-wave's 16 slots
+#pragma unroll
+    for (int rb = 0; rb < RB; rb++) {
+        const int gb = wv * RB + rb;
+        ub[rb] = (gb * 2 + hf) * UL;
+#pragma unroll
+        for (int i = 0; i < 16; i++) lr[rb][i] = lse[gb * 32 + 4 * hf + 8 * (i >> 2) + (i & 3)];
+    }
+    gload(0);
+    lstore(kbuf);
+    __syncthreads();
+#pragma unroll 1
+    for (int it = 0; it < ntiles; it++) {
+        const char *buf = kbuf + (it & 1) * KTl::BYTES;
+        float *pt = part + (it & 1) * NW * KT;
+        if (it + 1 < ntiles) gload(it + 1);
+        const int j0 = it * KT;
+        const bool edge = j0 + KT > u.Tv - w;
+#pragma unroll
+        for (int sub = 0; sub < KT / 32; sub++) {
+            f32x16 acc[RB];
+#pragma unroll
+            for (int rb = 0; rb < RB; rb++)
+#pragma unroll
+                for (int i = 0; i < 16; i++) acc[rb][i] = 0.f;
+            const char *kp = buf + (sub * 32 + l32) * KTl::ROW + hf * 16;
+#pragma unroll
+            for (int kk = 0; kk < KK; kk++) {
+                const bf16x8 kf = *(const bf16x8 *)(kp + kk * 32);
+#pragma unroll
+                for (int rb = 0; rb < RB; rb++) acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][kk], kf, acc[rb], 0, 0, 0);
+            }
+            // acc[rb][i]: slot i of this half-wave, key j = j0 + sub*32 + l32
+            const int j = j0 + sub * 32 + l32;
+            const int thr = j - (u.Tv - w);                   // window rows u < thr come before key j: hidden
+            float ps = 0.f;
+#pragma unroll
+            for (int rb = 0; rb < RB; rb++) {
+                float p[16];
+#pragma unroll
+                for (int i = 0; i < 16; i++) p[i] = fexp2(fmaf(acc[rb][i], c, -lr[rb][i]));
+                if (GT) {
+#pragma unroll
+                    for (int ul = 0; ul < (GT ? 16 / GT : 1); ul++) {
+                        float mx = p[ul * GT];
+#pragma unroll
+                        for (int g = 1; g < GT; g++) mx = fmaxf(mx, p[ul * GT + g]);
+                        if (edge && ub[rb] + ul < thr) mx = 0.f;
+                        ps += mx;
+                    }
+                } else {                                      // group size known only at run time
+                    float mx = 0.f;
+                    int g = 0, ul = 0;
+#pragma unroll
+                    for (int i = 0; i < 16; i++) {
+                        const float v = (edge && ub[rb] + ul < thr) ? 0.f : p[i];
+                        mx = fmaxf(mx, v);
+                        if (++g == G) { ps += mx; mx = 0.f; g = 0; ul++; }
+                    }
+                }
+            }
+            ps += __shfl_xor(ps, 32);
+            if (hf == 0) pt[wv * KT + sub * 32 + l32] = ps;
+        }
+        if (it + 1 < ntiles) lstore(kbuf + ((it + 1) & 1) * KTl::BYTES);
+        __syncthreads();
+        if (tid < KT) {                                       // fixed-order sum over the waves: deterministic
+            const int jj = j0 + tid;
+            if (jj < u.Tv) {
+                float s = 0.f;
+#pragma unroll
+                for (int v = 0; v < NW; v++) s += pt[v * KT + tid];
+                S[live_to_pos(u, a, jj)] = s / (float)w;
+            }
+        }
+    }
+    __syncthreads();
+    unit_tail(a, u, smem, tbl, dst, misc);
+}
+
+// (RB, NW) by the number of 32-row query blocks: small windows use fewer waves, large ones more rows per wave
+static void pick_geometry(int NB, int *NW, int *RB) {
+    if (NB <= 1) { *NW = 1; *RB = 1; }
+    else if (NB <= 2) { *NW = 2; *RB = 1; }
+    else if (NB <= 4) { *NW = 4; *RB = 1; }
+    else if (NB <= 8) { *NW = 4; *RB = 2; }
+    else if (NB <= 16) { *NW = 8; *RB = 2; }
+    else if (NB <= 24) { *NW = 8; *RB = 3; }
+    else { *NW = 8; *RB = 4; }
+}
+
+bool mfma_path_available(const Args &a, int *NW, int *RB) {
+    if (a.dtype != 1 || (a.d != 128 && a.d != 64)) return false;
+    if (a.G < 1 || a.G > 16) return false;
+    const int UL = 16 / a.G, NB = (a.w + 2 * UL - 1) / (2 * UL);
+    if (NB > 32) return false;
+    pick_geometry(NB, NW, RB);
+    return true;
+}
+
+template <int D, int RB, int NW>
+static hipError_t launch_g(const Args &a, int units, hipStream_t s) {
+    const dim3 grid(units), block(NW * 64);
+#define ZP_LAUNCH(GT)                                                                        \
+    {                                                                                        \
+        hipError_t e = allow_big_lds(unit_mfma<D, RB, NW, GT>);                              \
+        if (e != hipSuccess) return e;                                                       \
+        hipLaunchKernelGGL((unit_mfma<D, RB, NW, GT>), grid, block, a.lds_bytes, s, a);      \
+    }                                                                                        \
+    break;
+    switch (a.G) {
+        case 4: ZP_LAUNCH(4)
+        case 5: ZP_LAUNCH(5)
+        case 7: ZP_LAUNCH(7)
+        case 8: ZP_LAUNCH(8)
+        default: ZP_LAUNCH(0)
+    }
+#undef ZP_LAUNCH
+    return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_d(const Args &a, int units, int NW, int RB, hipStream_t s) {
+    if (RB == 1 && NW == 1) return launch_g<D, 1, 1>(a, units, s);
+    if (RB == 1 && NW == 2) return launch_g<D, 1, 2>(a, units, s);
+    if (RB == 1 && NW == 4) return launch_g<D, 1, 4>(a, units, s);
+    if (RB == 2 && NW == 4) return launch_g<D, 2, 4>(a, units, s);
+    if (RB == 2 && NW == 8) return launch_g<D, 2, 8>(a, units, s);
+    if (RB == 3 && NW == 8) return launch_g<D, 3, 8>(a, units, s);
+    if (RB == 4 && NW == 8) return launch_g<D, 4, 8>(a, units, s);
+    return hipErrorInvalidConfiguration;
+}
+
+hipError_t launch_unit_mfma(const Args &a, int units, int NW, int RB, hipStream_t s) {
+    if (units <= 0) return hipSuccess;
+    if (a.d == 128) return launch_d<128>(a, units, NW, RB, s);
+    if (a.d == 64) return launch_d<64>(a, units, NW, RB, s);
+    return hipErrorInvalidConfiguration;
+}
+
+}  // namespace zp

@@ -1,0 +1,223 @@
+"""GPU tests of the single stages (selection on hand-made scores, compaction on adversarial kept sets,
+copy-on-write targets) and of the error behaviour of the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2603_08743_amd import binding, workloads
+from tests import gpu_util as G
+from tests.util import random_problem
+
+pytestmark = pytest.mark.gpu
+
+
+def select_on_device(p, scores):
+    pool, batch = G.to_device(p)
+    _, keep_idx, ln = G.alloc_outputs(pool, batch)
+    s = torch.from_numpy(np.ascontiguousarray(scores, dtype=np.float32)).cuda()
+    G.ctx().zp_select_topk(s, pool, batch, keep_idx, ln)
+    G.ctx().zp_sync_status()
+    return keep_idx.cpu().numpy(), ln.cpu().numpy()
+
+
+@pytest.mark.parametrize("case", ["random", "all_equal", "two_values", "specials", "descending", "ascending", "tiny_diffs"])
+def test_select_matches_oracle_on_handmade_scores(case):
+    rng = np.random.default_rng(7)
+    B, L, H, b, N_max, w, extra = 2, 2, 3, 16, 9, 5, 2
+    p = random_problem(1, B=B, L=L, h_kv=H, G=1, d=8, b=b, N_max=N_max, w=w, extra_blocks=extra)
+    T = (N_max + extra) * b
+    shape = (B, L, H, T)
+    if case == "random":
+        S = rng.random(shape)
+    elif case == "all_equal":
+        S = np.full(shape, 0.25)
+    elif case == "two_values":
+        S = rng.integers(0, 2, size=shape) * 0.5
+    elif case == "specials":
+        S = rng.standard_normal(shape)
+        flat = S.reshape(-1)
+        for v in (np.nan, np.inf, -np.inf, 0.0, -0.0, 1e-42, -1e-42):
+            flat[rng.integers(0, flat.size, 60)] = v
+    elif case == "descending":
+        S = np.broadcast_to(np.linspace(1, 0, T), shape).copy()
+    elif case == "ascending":
+        S = np.broadcast_to(np.linspace(0, 1, T), shape).copy()
+    else:
+        S = 1.0 + rng.integers(0, 4, size=shape) * np.float32(1.1920929e-07)    # neighbours in fp32
+    S = S.astype(np.float32)
+    p.keep = rng.integers(w, (N_max - 1) * b + 1, size=(B, L, H)).astype(np.int32)
+    p.keep[0, 0, 0], p.keep[0, 0, 1] = w, (N_max - 1) * b
+    want_idx, want_len = oracle.select(p, S)
+    got_idx, got_len = select_on_device(p, S)
+    assert np.array_equal(got_len, want_len) and np.array_equal(got_idx, want_idx)
+
+
+def test_select_with_stale_gap_and_long_row_stride():
+    rng = np.random.default_rng(3)
+    p = random_problem(2, B=1, L=1, h_kv=2, G=1, d=8, b=8, N_max=4, w=12, extra_blocks=3)
+    p.valid_len = np.array([[[17, 40]]], dtype=np.int32)
+    p.keep = np.array([[[20, 24]]], dtype=np.int32)
+    S = rng.random((1, 1, 2, 7 * 8 + 13)).astype(np.float32)           # row stride larger than max_blocks*b
+    want_idx, want_len = oracle.select(p, S)
+    got_idx, got_len = select_on_device(p, S)
+    assert np.array_equal(got_idx, want_idx) and np.array_equal(got_len, want_len)
+
+
+def compact_on_device(p, idx, ln):
+    pool, batch = G.to_device(p)
+    G.ctx().zp_compact_kv(pool, batch, torch.from_numpy(idx).cuda(), torch.from_numpy(ln).cuda())
+    G.ctx().zp_sync_status()
+    return G.pool_bits(pool.k), G.pool_bits(pool.v)
+
+
+@pytest.mark.parametrize("pattern", ["keep_all_prefix", "only_tail", "every_bth", "random", "shift_by_one", "empty_and_full"])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_compact_adversarial_kept_sets(pattern, bf16):
+    rng = np.random.default_rng(11)
+    B, L, H, b, N_max, extra = 2, 2, 2, 16, 20, 6          # several chunks of 64 rows per unit, ragged tail
+    p = random_problem(5, B=B, L=L, h_kv=H, G=1, d=128 if bf16 else 64, b=b, N_max=N_max, w=4, extra_blocks=extra, bf16=bf16)
+    T, budget = (N_max + extra) * b, (N_max - 1) * b
+    idx = np.full((B, L, H, budget), -1, dtype=np.int32)
+    ln = np.zeros((B, L, H), dtype=np.int32)
+    for n in range(B):
+        for l in range(L):
+            for h in range(H):
+                if pattern == "keep_all_prefix":
+                    sel = np.arange(budget)
+                elif pattern == "only_tail":
+                    sel = np.arange(T - budget, T)
+                elif pattern == "every_bth":
+                    sel = np.arange(0, T, b)[:budget]
+                elif pattern == "random":
+                    sel = np.sort(rng.choice(T, size=int(rng.integers(1, budget + 1)), replace=False))
+                elif pattern == "shift_by_one":
+                    sel = np.arange(1, budget + 1)                   # every row moves down by one slot: maximal aliasing
+                else:
+                    sel = np.arange(0) if (n + l + h) % 2 else np.sort(rng.choice(T, size=budget, replace=False))
+                idx[n, l, h, : sel.size] = sel
+                ln[n, l, h] = sel.size
+    q = oracle.Problem(K=p.K.copy(), V=p.V.copy(), Q=p.Q, block_table=p.block_table, num_blocks=p.num_blocks, q_slot=p.q_slot, N_max=N_max)
+    oracle.compact(q, idx, ln)
+    Kd, Vd = compact_on_device(p, idx, ln)
+    assert np.array_equal(Kd, q.K) and np.array_equal(Vd, q.V)       # whole pool: bystanders and stale tails untouched
+
+
+def test_prefix_sharing_copy_on_write_end_to_end():
+    # reduced prefix-cache mix: plan on the host, compress into the planned targets, check refcounts, freed list, shared bytes
+    w = workloads.config(3, B=12, L=1, N_total=12 * 257 + 400, compress_frac=0.5)
+    p, pool, batch = G.workload_problem(w)
+    refcnt = w.refcnt.copy()
+    plan = binding.zp_plan(w.block_table, w.num_blocks, w.N_max, refcnt, w.free_list)
+    want = oracle.plan(w.block_table, w.num_blocks, w.N_max, w.refcnt, w.free_list)
+    assert np.array_equal(plan["dst_table"], want["dst_table"]) and np.array_equal(plan["freed"], want["freed"])
+    assert np.array_equal(refcnt, want["refcnt"]) and plan["n_free_used"] == want["n_free_used"]
+    shared = np.flatnonzero(w.refcnt > 1)
+    assert shared.size == 64 and plan["n_free_used"] == 64 * sum(1 for n in range(w.B) if w.refcnt[w.block_table[n, 0]] > 1)
+    p.dst_table = plan["dst_table"]
+    batch.dst_table = G.dev_i32(plan["dst_table"])
+    G.ctx().zp_validate_batch(pool, batch)
+    K0 = p.K.copy()
+    rep = G.full_protocol(p, pool, batch)
+    assert rep["worst_rel"] < 1e-3
+    fused = G.clone_pool(pool)
+    G.run_fused(fused, batch, debug=False)
+    Kd = G.pool_bits(fused.k)
+    assert np.array_equal(Kd[:, shared], K0[:, shared])               # shared prefix blocks are never written
+    for t in w.bystander_tables:
+        assert np.array_equal(Kd[:, t], K0[:, t])
+
+
+def test_host_argument_errors():
+    c = G.ctx()
+    p = random_problem(1, B=1, L=1, h_kv=2, G=2, d=8, b=4, N_max=3, w=2)
+    pool, batch = G.to_device(p)
+    scores, keep_idx, ln = G.alloc_outputs(pool, batch)
+
+    def status_of(fn):
+        with pytest.raises(binding.ZpError) as e:
+            fn()
+        return e.value.status
+
+    bad = binding.Batch(block_table=batch.block_table, num_blocks=batch.num_blocks, q_slot=batch.q_slot, N_max=1, L=1)
+    assert status_of(lambda: c.zp_score(pool, bad, scores)) == binding.ZP_EINVAL
+    bad = binding.Batch(block_table=batch.block_table, num_blocks=batch.num_blocks, q_slot=batch.q_slot, N_max=4, L=1)   # max_blocks < N_max
+    assert status_of(lambda: c.zp_compress(pool, bad, ln)) == binding.ZP_EINVAL
+    bad = binding.Batch(block_table=batch.block_table, num_blocks=batch.num_blocks, q_slot=batch.q_slot, N_max=3, L=0)   # L < layer0 + L_slab
+    assert status_of(lambda: c.zp_compress(pool, bad, ln)) == binding.ZP_EINVAL
+    odd = binding.Pool(k=torch.zeros(1, 8, 4, 2, 6, device="cuda"), v=torch.zeros(1, 8, 4, 2, 6, device="cuda"), q=torch.zeros(1, 2, 2, 4, 6, device="cuda"))
+    assert status_of(lambda: c.zp_score(odd, batch, torch.zeros(1, 1, 2, 12, device="cuda"))) == binding.ZP_EUNSUPPORTED   # 24-byte rows
+    big = binding.Batch(block_table=torch.zeros(1, 20000, dtype=torch.int32, device="cuda"), num_blocks=batch.num_blocks, q_slot=batch.q_slot, N_max=3, L=1)
+    assert status_of(lambda: c.zp_compress(pool, big, ln)) == binding.ZP_EUNSUPPORTED
+    hq = binding.Pool(k=pool.k, v=pool.v, q=torch.zeros(1, 2, 2, 3, 8, device="cuda"))                                   # h_q = 3, h_kv = 2
+    assert status_of(lambda: c.zp_score(hq, batch, scores)) == binding.ZP_EUNSUPPORTED
+    wide = binding.Pool(k=pool.k, v=pool.v, q=torch.zeros(1, 2, 9, 4, 8, device="cuda"))                                 # w = 9 > budget 8
+    assert status_of(lambda: c.zp_score(wide, batch, scores)) == binding.ZP_EINVAL
+    assert "budget" in c.lib.zp_last_error(c.h).decode()
+
+
+@pytest.mark.parametrize("what", ["block_id", "num_blocks", "keep", "valid_len", "slot", "keep_idx"])
+def test_bad_table_contents_are_skipped_and_reported(what):
+    c = G.ctx()
+    p = random_problem(2, B=2, L=1, h_kv=2, G=2, d=8, b=4, N_max=3, w=2, extra_blocks=1)
+    K0 = p.K.copy()
+    if what == "block_id":
+        p.block_table[1, 2] = p.K.shape[1] + 5
+    elif what == "num_blocks":
+        p.num_blocks[1] = 2
+    elif what == "keep":
+        p.keep = np.array([[[8, 8]], [[8, 1]]], dtype=np.int32)
+    elif what == "valid_len":
+        p.valid_len = np.array([[[12, 12]], [[12, 13]]], dtype=np.int32)
+    elif what == "slot":
+        p.q_slot[1] = 77
+    pool, batch = G.to_device(p)
+    scores, keep_idx, ln = G.alloc_outputs(pool, batch)
+    if what == "keep_idx":
+        idx = np.tile(np.arange(8, dtype=np.int32), (2, 1, 2, 1))
+        idx[1, 0, 1, 3] = 2                                            # not ascending
+        c.zp_compact_kv(pool, batch, torch.from_numpy(idx).cuda(), torch.full((2, 1, 2), 8, dtype=torch.int32, device="cuda"))
+    else:
+        c.zp_compress(pool, batch, ln, scores, keep_idx)
+    with pytest.raises(binding.ZpError) as e:
+        c.zp_sync_status()
+    assert e.value.status == binding.ZP_EINVAL and "skipped unit" in str(e.value)
+    c.zp_sync_status()                                                 # the flag is cleared by the report
+    if what != "keep_idx":
+        lh = ln.cpu().numpy()
+        assert (lh[0] == 8).all() and (lh[1] == -1).any()              # good units done, bad ones marked
+        with pytest.raises(binding.ZpError):
+            c.zp_validate_batch(pool, batch)
+    # blocks of the good request are compacted, nothing outside the batch's blocks changed
+    Kd = G.pool_bits(pool.k)
+    others = np.setdiff1d(np.arange(p.K.shape[1]), np.clip(p.block_table, 0, p.K.shape[1] - 1).reshape(-1))
+    assert np.array_equal(Kd[:, others], K0[:, others])
+
+
+def test_validate_batch_rules():
+    c = G.ctx()
+    p = random_problem(3, B=2, L=1, h_kv=1, G=1, d=8, b=4, N_max=3, w=2, extra_blocks=1, N_total=20)
+    pool, batch = G.to_device(p)
+    c.zp_validate_batch(pool, batch)
+    dst = p.block_table[:, :2].copy()
+    dst[0, 0] = p.block_table[1, 3]                                    # a target that is another request's source block
+    batch.dst_table = G.dev_i32(dst)
+    with pytest.raises(binding.ZpError):
+        c.zp_validate_batch(pool, batch)
+    tbl = p.block_table.copy()
+    tbl[0, 1] = tbl[0, 0]                                              # duplicate block in a table
+    batch.dst_table = None
+    batch.block_table = G.dev_i32(tbl)
+    with pytest.raises(binding.ZpError):
+        c.zp_validate_batch(pool, batch)
+
+
+def test_empty_batch_is_a_no_op():
+    c = G.ctx()
+    p = random_problem(4, B=1, L=1, h_kv=1, G=1, d=8, b=4, N_max=3, w=2)
+    pool, _ = G.to_device(p)
+    empty = binding.Batch(block_table=torch.zeros(0, 3, dtype=torch.int32, device="cuda"), num_blocks=torch.zeros(0, dtype=torch.int32, device="cuda"),
+                          q_slot=torch.zeros(0, dtype=torch.int32, device="cuda"), N_max=3, L=1)
+    c.zp_compress(pool, empty, torch.zeros(0, dtype=torch.int32, device="cuda"))
+    c.zp_sync_status()
+    assert np.array_equal(G.pool_bits(pool.k), p.K)
