@@ -36,6 +36,12 @@ def build(verbose: bool = False) -> str:
     if r.returncode:
         raise RuntimeError("link failed:\n" + r.stderr)
     os.replace(tmp, LIB)
+    # stand-alone counter/timing driver, linked against the library it measures
+    drv = os.path.join(HERE, "zp_prof_driver")
+    r = subprocess.run(["hipcc", *FLAGS, os.path.join(CSRC, "zp_prof_driver.hip"), "-o", drv, "-L" + HERE, "-lzp", "-Wl,-rpath,$ORIGIN"],
+                       capture_output=True, text=True)
+    if r.returncode:
+        raise RuntimeError("driver build failed:\n" + r.stderr)
     return LIB
 
 
