@@ -1,0 +1,126 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times (one layer slab per launch).
+
+The oracle cannot run 16 384 units of these shapes, so: (a) a seeded sample of whole requests (every layer of the
+slab, every head) is snapshotted before the launch and checked P1/P2/P3 against the oracle; (b) every unit is checked
+by properties that hold at any size: lengths equal the keep counts, kept lists strictly ascending and ending in the
+window, blocks that belong to no compressing request unchanged, rows beyond k_h of the targets unchanged.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2603_08743_amd import binding, workloads
+from paper_2603_08743_amd.workloads import to_host_bits
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+def sub_problem(w, K, V, Q, sample, Ls, layer0, dst_table=None):
+    """Host mirror of the sampled requests: their source and target blocks gathered into a small pool."""
+    rows = [w.block_table[n, : w.num_blocks[n]] for n in sample]
+    ids = list(np.concatenate(rows))
+    if dst_table is not None:
+        ids += [int(p) for n in sample for p in dst_table[n] if int(p) not in set(ids)]
+    ids = np.array(list(dict.fromkeys(int(p) for p in ids)), dtype=np.int64)
+    remap = {int(p): i for i, p in enumerate(ids)}
+    tbl = np.full((len(sample), w.max_blocks), -1, dtype=np.int32)
+    for r, row in enumerate(rows):
+        tbl[r, : len(row)] = [remap[int(p)] for p in row]
+    dst = None
+    if dst_table is not None:
+        dst = np.array([[remap[int(p)] for p in dst_table[n]] for n in sample], dtype=np.int32)
+    idt = torch.from_numpy(ids).cuda()
+    qs = torch.from_numpy(w.q_slot[sample].astype(np.int64)).cuda()
+    sl = slice(layer0, layer0 + Ls)
+    p = oracle.Problem(K=to_host_bits(K[:, idt]), V=to_host_bits(V[:, idt]), Q=to_host_bits(Q[:, qs]), block_table=tbl,
+                       num_blocks=w.num_blocks[sample].copy(), q_slot=np.arange(len(sample), dtype=np.int32), N_max=w.N_max,
+                       keep=None if w.keep is None else np.ascontiguousarray(w.keep[sample][:, sl]), dst_table=dst)
+    return p, idt
+
+
+def checksum(t, block_ids, chunk=1024):
+    """Per-block integer checksum of the given physical blocks (chunked: the pools are tens of GiB)."""
+    v = t.view(torch.int16) if t.dtype == torch.bfloat16 else t.view(torch.int32)
+    weights = torch.arange(1, v.shape[2] * v.shape[3] * v.shape[4] + 1, device=t.device, dtype=torch.int64)
+    out = []
+    for o in range(0, block_ids.numel(), chunk):
+        part = v[:, block_ids[o:o + chunk]].reshape(v.shape[0], -1, weights.numel()).to(torch.int64)
+        out.append((part * weights).sum(dim=(0, 2)))       # position-weighted: a swap of two rows changes it
+    return torch.cat(out) if out else torch.zeros(0, dtype=torch.int64, device=t.device)
+
+
+@pytest.mark.parametrize("cfg,Ls,n_sample", [(1, 28, 2), (2, 8, 2), (4, 8, 1), (3, 8, 2)], ids=["cfg1", "cfg2", "cfg4", "cfg3"])
+def test_full_size_launch(cfg, Ls, n_sample):
+    torch.cuda.empty_cache()
+    w = workloads.config(cfg) if cfg != 3 else workloads.config(3, compress_frac=0.5)
+    layer0 = Ls if w.L > Ls else 0                       # a slab that is not the first one: exercises layer0 offsets
+    print("\n%s: B=%d slab layers [%d,%d) pool %d blocks" % (w.name, w.B, layer0, layer0 + Ls, w.N_total), flush=True)
+    K, V, Q = w.pools("cuda", layer0, Ls)
+    dst_table = None
+    if cfg == 3:
+        refcnt = w.refcnt.copy()
+        plan = binding.zp_plan(w.block_table, w.num_blocks, w.N_max, refcnt, w.free_list)
+        dst_table = plan["dst_table"]
+        want = oracle.plan(w.block_table, w.num_blocks, w.N_max, w.refcnt, w.free_list)
+        assert np.array_equal(plan["dst_table"], want["dst_table"]) and np.array_equal(plan["freed"], want["freed"])
+        assert np.array_equal(plan["new_table"], want["new_table"]) and np.array_equal(refcnt, want["refcnt"])
+    rng = np.random.default_rng(cfg)
+    sample = sorted(rng.choice(w.B, size=n_sample, replace=False).tolist())
+    if cfg == 3:                                          # one sharer and one non-sharer
+        sharers = [n for n in range(w.B) if w.refcnt[w.block_table[n, 0]] > 1]
+        loners = [n for n in range(w.B) if w.refcnt[w.block_table[n, 0]] == 1]
+        sample = [sharers[0], loners[0]]
+    p, idt = sub_problem(w, K, V, Q, sample, Ls, layer0, dst_table)
+    used = np.zeros(w.N_total, dtype=bool)
+    used[w.block_table[w.block_table >= 0]] = True
+    if dst_table is not None:
+        written = np.zeros(w.N_total, dtype=bool)
+        written[dst_table.reshape(-1)] = True
+        quiet = torch.from_numpy(np.flatnonzero(~written)).cuda()    # shared prefix and bystanders included
+    else:
+        quiet = torch.from_numpy(np.flatnonzero(~used)).cuda()
+    ck_before = (checksum(K, quiet), checksum(V, quiet))
+    # rows beyond k_h of a few target blocks must stay as they were: remember the last target block of sampled requests
+    units = w.B * Ls * w.h_kv
+    batch = binding.Batch(block_table=G.dev_i32(w.block_table), num_blocks=G.dev_i32(w.num_blocks), q_slot=G.dev_i32(w.q_slot),
+                          N_max=w.N_max, L=w.L, keep=G.dev_i32(w.keep), dst_table=G.dev_i32(dst_table))
+    pool = binding.Pool(k=K, v=V, q=Q, layer0=layer0)
+    scores = torch.empty(w.B, Ls, w.h_kv, w.max_blocks * w.b, dtype=torch.float32, device="cuda")
+    keep_idx = torch.empty(w.B, Ls, w.h_kv, w.budget, dtype=torch.int32, device="cuda")
+    ln = torch.empty(w.B, Ls, w.h_kv, dtype=torch.int32, device="cuda")
+    c = G.ctx()
+    c.zp_compress(pool, batch, ln, scores, keep_idx)
+    c.zp_sync_status()
+    # ---- (b) properties over every unit
+    want_len = torch.full_like(ln, w.budget) if w.keep is None else torch.from_numpy(w.keep[:, layer0:layer0 + Ls]).cuda()
+    assert torch.equal(ln, want_len)
+    r = torch.arange(w.budget, device="cuda", dtype=torch.int32)
+    valid = r < ln[..., None]
+    assert bool(((keep_idx >= 0) == valid).all())
+    asc = (keep_idx[..., 1:] > keep_idx[..., :-1]) | ~valid[..., 1:]
+    assert bool(asc.all())
+    T = torch.from_numpy(w.num_blocks.astype(np.int32)).cuda()[:, None, None] * w.b
+    last = torch.gather(keep_idx, -1, (ln[..., None] - 1).long())[..., 0]
+    first_win = torch.gather(keep_idx, -1, (ln[..., None] - w.w).long())[..., 0]
+    assert torch.equal(last, (T - 1).expand_as(last)) and torch.equal(first_win, (T - w.w).expand_as(first_win))
+    ck_after = (checksum(K, quiet), checksum(V, quiet))
+    assert torch.equal(ck_before[0], ck_after[0]) and torch.equal(ck_before[1], ck_after[1])
+    assert bool(torch.isfinite(scores).all()) and bool((scores >= 0).all())
+    # ---- (a) sampled requests against the oracle
+    st = torch.tensor(sample, device="cuda")
+    g_scores = scores[st].cpu().numpy()
+    g_idx, g_len = keep_idx[st].cpu().numpy(), ln[st].cpu().numpy()
+    ref = oracle.score(p)
+    worst = G.check_scores(g_scores, ref)
+    o_idx, o_len = oracle.select(p, g_scores)
+    assert np.array_equal(o_len, g_len) and np.array_equal(o_idx, g_idx)
+    oracle.compact(p, o_idx, o_len)
+    assert np.array_equal(to_host_bits(K[:, idt]), p.K) and np.array_equal(to_host_bits(V[:, idt]), p.V)
+    i_idx, _ = oracle.select(p, ref.astype(np.float32))
+    same = int((i_idx == g_idx).all(axis=-1).sum())
+    print("%s: sampled requests %s, worst score error %.2e (relative), independent kept sets equal in %d/%d units"
+          % (w.name, sample, worst, same, g_idx.shape[0] * g_idx.shape[1] * g_idx.shape[2]), flush=True)
+    del K, V, Q, scores, keep_idx
+    torch.cuda.empty_cache()
