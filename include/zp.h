@@ -97,9 +97,19 @@ zp_status zp_create(zp_ctx **out);
 void zp_destroy(zp_ctx *ctx);
 const char *zp_last_error(const zp_ctx *ctx); /* ctx may be NULL: text of the last failed zp_create/zp_plan */
 
-/* Device scratch the calls below need beyond inputs and outputs (currently only the
-   context's status words; nothing is allocated per call). */
+/* Device scratch zp_score / zp_compress need beyond inputs and outputs for this shape when ZP_OPT_SPLIT
+   is 1: exchange buffers between the workgroups that share a unit (0 if the shape cannot be split).
+   The context allocates it on the first call that needs more than it holds and keeps it; calls
+   on one context must therefore not overlap on different streams. */
 size_t zp_scratch_bytes(const zp_pool *pool, const zp_batch *batch);
+
+/* Tuning / test switches.  ZP_OPT_SPLIT: -1 automatic (default; currently the same as 0), 0 one workgroup per
+   unit (keys swept twice from HBM), 1 several workgroups per unit with LDS-resident key chunks whenever the
+   shape allows (keys read from HBM once; needs the scratch zp_scratch_bytes reports).
+   ZP_OPT_SPIN_LIMIT: bound on the wait loop of the split path (iterations, > 0).
+   ZP_OPT_STREAMS: cap (1..8) on the ticket streams the split path orders its workgroups by. */
+typedef enum { ZP_OPT_SPLIT = 1, ZP_OPT_SPIN_LIMIT = 2, ZP_OPT_STREAMS = 3 } zp_option;
+zp_status zp_set_option(zp_ctx *ctx, int32_t option, int32_t value);
 
 /*
  * Step (1).  scores: [dev] fp32 [B][L_slab][h_kv][T_max], T_max = max_blocks*b.

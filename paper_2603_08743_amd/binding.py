@@ -18,9 +18,10 @@ LIB_PATH = os.path.join(_HERE, "libzp.so")
 
 ZP_OK, ZP_EINVAL, ZP_ENOMEM, ZP_EHIP, ZP_EUNSUPPORTED = 0, -1, -2, -3, -4
 ZP_F32, ZP_BF16 = 0, 1
+ZP_OPT_SPLIT, ZP_OPT_SPIN_LIMIT, ZP_OPT_STREAMS = 1, 2, 3
 
 EXPORTS = ("zp_create", "zp_destroy", "zp_last_error", "zp_scratch_bytes", "zp_score", "zp_select_topk", "zp_compact_kv",
-           "zp_compress", "zp_sync_status", "zp_validate_batch", "zp_plan")
+           "zp_compress", "zp_sync_status", "zp_validate_batch", "zp_plan", "zp_set_option")
 
 
 class ZpError(RuntimeError):
@@ -172,6 +173,9 @@ class Context:
         self._check(self.lib.zp_compress(self.h, ctypes.byref(p), ctypes.byref(b), ctypes.c_void_p(len_out.data_ptr()),
                                          ctypes.c_void_p(scores_dbg.data_ptr() if scores_dbg is not None else None),
                                          ctypes.c_void_p(keep_idx_dbg.data_ptr() if keep_idx_dbg is not None else None), _stream()))
+
+    def zp_set_option(self, option: int, value: int) -> None:
+        self._check(self.lib.zp_set_option(self.h, ctypes.c_int32(option), ctypes.c_int32(value)))
 
     def zp_sync_status(self) -> None:
         self._check(self.lib.zp_sync_status(self.h, _stream()))

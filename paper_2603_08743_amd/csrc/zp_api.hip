@@ -16,6 +16,12 @@ struct zp_ctx {
     int device;
     int *d_status;   // 4 words on the device
     int *h_status;   // pinned mirror
+    char *scratch;   // exchange buffers of the split path, grown on demand (never shrunk)
+    size_t scratch_bytes;
+    int split_mode;  // -1 auto, 0 never, 1 whenever the shape allows
+    int spin_limit;
+    int max_streams; // cap on the ticket streams of the split path
+    int n_cu;        // compute units: every kernel here fits at least one workgroup per CU
     char err[512];
 };
 
@@ -42,6 +48,14 @@ extern "C" zp_status zp_create(zp_ctx **out) {
     if (!c) return fail(nullptr, ZP_ENOMEM, "zp_create: out of host memory");
     c->device = dev;
     c->err[0] = 0;
+    c->scratch = nullptr;
+    c->scratch_bytes = 0;
+    c->split_mode = -1;
+    c->spin_limit = 1 << 21;
+    c->max_streams = 8;
+    c->n_cu = 0;
+    (void)hipDeviceGetAttribute(&c->n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+    if (c->n_cu <= 0) c->n_cu = 64;
     if ((e = hipMalloc((void **)&c->d_status, 4 * sizeof(int))) != hipSuccess ||
         (e = hipHostMalloc((void **)&c->h_status, 4 * sizeof(int), hipHostMallocDefault)) != hipSuccess ||
         (e = hipMemset(c->d_status, 0, 4 * sizeof(int))) != hipSuccess) {
@@ -58,15 +72,35 @@ extern "C" void zp_destroy(zp_ctx *ctx) {
     if (!ctx) return;
     (void)hipFree(ctx->d_status);
     (void)hipHostFree(ctx->h_status);
+    if (ctx->scratch) (void)hipFree(ctx->scratch);
     delete ctx;
 }
 
-extern "C" size_t zp_scratch_bytes(const zp_pool *, const zp_batch *) { return 4 * sizeof(int); }
-
 static int align16(int x) { return (x + 15) & ~15; }
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 static const int kLdsLimit = 160 * 1024;
 
-enum Path { PATH_GENERIC, PATH_MFMA };
+enum Path { PATH_GENERIC, PATH_MFMA, PATH_SPLIT };
+
+// Exchange buffers of the split path: [sync words][per-chunk (max,sum)][log-sum-exp][scores].
+struct SplitLayout { size_t off_partial, off_lse, off_sbuf, total; };
+static SplitLayout split_layout(long long units, int C, int RP, int T_max) {
+    SplitLayout l;
+    l.off_partial = align256((size_t)(256 + 3 * units) * sizeof(int));
+    l.off_lse = l.off_partial + align256((size_t)units * C * RP * sizeof(float2));
+    l.off_sbuf = l.off_lse + align256((size_t)units * RP * sizeof(float));
+    l.total = l.off_sbuf + align256((size_t)units * T_max * sizeof(float));
+    return l;
+}
+
+extern "C" zp_status zp_set_option(zp_ctx *ctx, int32_t option, int32_t value) {
+    if (!ctx) return ZP_EINVAL;
+    if (option == ZP_OPT_SPLIT && value >= -1 && value <= 1) { ctx->split_mode = value; return ZP_OK; }
+    if (option == ZP_OPT_SPIN_LIMIT && value > 0) { ctx->spin_limit = value; return ZP_OK; }
+    if (option == ZP_OPT_STREAMS && value >= 1 && value <= 8) { ctx->max_streams = value; return ZP_OK; }
+    snprintf(ctx->err, sizeof(ctx->err), "zp_set_option: unknown option %d or bad value %d", option, value);
+    return ZP_EINVAL;
+}
 
 // Scalar checks shared by every call, and the kernel argument block.  `need_q`: the call scores.
 static zp_status prepare(zp_ctx *ctx, const char *who, const zp_pool *p, const zp_batch *b, bool need_q, zp::Args *a,
@@ -116,11 +150,39 @@ static zp_status prepare(zp_ctx *ctx, const char *who, const zp_pool *p, const z
     }
     if (!need_q) score_bytes = 0;
     const size_t list_bytes = (size_t)a->budget * 4;
+    const int misc_bytes = align16((int)sizeof(int) * (256 + 16 + 4));
+    // automatic = one workgroup per unit: measured on MI355X, the split path is bound by the latency of its
+    // exchange steps (20 ms against 12.5 ms for the scoring of one 8-layer slab of the 8B-like shape)
+    if (*path == PATH_MFMA && ctx->split_mode == 1) {
+        // split path: misc first, then either (key chunk, wave partials) or (S, tables, kept list)
+        const int nsub_max = (a->T_max + 31) / 32;
+        a->C = (nsub_max + zp::SPLIT_SUBS - 1) / zp::SPLIT_SUBS;
+        // ticket streams: at most NS*(C-1) workgroups can ever be waiting for peers that have not started;
+        // keep that below a quarter of the workgroups the chip should hold (one per CU; a run with 8-wave
+        // workgroups showed that as few as half of them can be resident, so leave a factor of two)
+        a->NS = 1;
+        for (int ns = 8; ns > 1; ns >>= 1)
+            if (ns <= ctx->max_streams && units % ns == 0 && (long long)ns * (a->C - 1) <= (ctx->n_cu > 0 ? ctx->n_cu : 64) / 4) { a->NS = ns; break; }
+        a->RP = *NW * *RB * 32;
+        a->spin_limit = ctx->spin_limit;
+        const int chunk_bytes = zp::SPLIT_SUBS * 32 * a->d * 2, part_bytes = *NW * zp::SPLIT_SUBS * 32 * 4;
+        const int t_S = misc_bytes, t_tbl = t_S + align16(a->T_max * 4), t_dst = t_tbl + align16(a->max_blocks * 4);
+        const int t_union = t_dst + align16((a->N_max - 1) * 4);
+        const size_t tail_total = (size_t)t_union + list_bytes, split_total = (size_t)misc_bytes + chunk_bytes + part_bytes;
+        const size_t total = tail_total > split_total ? tail_total : split_total;
+        if (total <= (size_t)kLdsLimit && units * a->C <= 0x7fffffffLL && a->C - 1 <= (ctx->n_cu > 0 ? ctx->n_cu : 64) / 2) {
+            *path = PATH_SPLIT;
+            a->off_misc = 0; a->off_S = t_S; a->off_tbl = t_tbl; a->off_dst = t_dst; a->off_union = t_union;
+            a->off_chunk = misc_bytes; a->off_part = misc_bytes + chunk_bytes;
+            a->lds_bytes = align16((int)total);
+            return ZP_OK;
+        }
+    }
     a->off_S = 0;
     a->off_tbl = align16(a->T_max * 4);
     a->off_dst = a->off_tbl + align16(a->max_blocks * 4);
     a->off_misc = a->off_dst + align16((a->N_max - 1) * 4);
-    a->off_union = a->off_misc + align16((int)sizeof(int) * (256 + 16 + 4));
+    a->off_union = a->off_misc + misc_bytes;
     const size_t total = (size_t)a->off_union + (score_bytes > list_bytes ? score_bytes : list_bytes);
     if (total > (size_t)kLdsLimit)
         return fail(ctx, ZP_EUNSUPPORTED, "%s: %zu bytes of LDS per unit exceed %d (max_blocks*b too large)", who, total, kLdsLimit);
@@ -128,10 +190,38 @@ static zp_status prepare(zp_ctx *ctx, const char *who, const zp_pool *p, const z
     return ZP_OK;
 }
 
-static zp_status launch(zp_ctx *ctx, const char *who, const zp::Args &a, Path path, int NW, int RB, void *stream) {
+extern "C" size_t zp_scratch_bytes(const zp_pool *pool, const zp_batch *batch) {
+    zp_ctx tmp;
+    memset(&tmp, 0, sizeof(tmp));
+    tmp.split_mode = 1;
+    tmp.max_streams = 1;
+    zp::Args a; Path path; int NW, RB;
+    if (prepare(&tmp, "zp_scratch_bytes", pool, batch, true, &a, &path, &NW, &RB) != ZP_OK || path != PATH_SPLIT) return 0;
+    return split_layout((long long)a.B * a.L_slab * a.h_kv, a.C, a.RP, a.T_max).total;
+}
+
+static zp_status launch(zp_ctx *ctx, const char *who, zp::Args &a, Path path, int NW, int RB, void *stream) {
     const int units = a.B * a.L_slab * a.h_kv;
-    hipError_t e = path == PATH_MFMA ? zp::launch_unit_mfma(a, units, NW, RB, (hipStream_t)stream)
-                                     : zp::launch_unit_generic(a, units, (hipStream_t)stream);
+    hipError_t e;
+    if (path == PATH_SPLIT && units > 0) {
+        const SplitLayout l = split_layout(units, a.C, a.RP, a.T_max);
+        if (l.total > ctx->scratch_bytes) {               // grow (first use of a larger shape only); hipFree waits for the device
+            if (ctx->scratch) (void)hipFree(ctx->scratch);
+            ctx->scratch = nullptr;
+            ctx->scratch_bytes = 0;
+            if ((e = hipMalloc((void **)&ctx->scratch, l.total)) != hipSuccess)
+                return fail(ctx, ZP_ENOMEM, "%s: cannot allocate %zu bytes of exchange scratch: %s", who, l.total, hipGetErrorString(e));
+            ctx->scratch_bytes = l.total;
+        }
+        a.sync = (int *)ctx->scratch;
+        a.partial = (float2 *)(ctx->scratch + l.off_partial);
+        a.lse_g = (float *)(ctx->scratch + l.off_lse);
+        a.sbuf = (float *)(ctx->scratch + l.off_sbuf);
+        e = zp::launch_zero_words(a.sync, 256 + 3 * units, (hipStream_t)stream);
+        if (e == hipSuccess) e = zp::launch_unit_split(a, units, NW, RB, (hipStream_t)stream);
+    } else
+    e = path == PATH_MFMA ? zp::launch_unit_mfma(a, units, NW, RB, (hipStream_t)stream)
+                          : zp::launch_unit_generic(a, units, (hipStream_t)stream);
     if (e != hipSuccess) return fail(ctx, ZP_EHIP, "%s: kernel launch failed: %s", who, hipGetErrorString(e));
     return ZP_OK;
 }
@@ -192,8 +282,9 @@ extern "C" zp_status zp_sync_status(zp_ctx *ctx, void *stream) {
     e = hipMemsetAsync(ctx->d_status, 0, 4 * sizeof(int), s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     static const char *names[] = {"?", "num_blocks outside [N_max, max_blocks]", "valid_len out of range", "keep count out of range",
-                                  "query slot out of range", "block id out of range", "keep_idx not ascending or out of range"};
-    return fail(ctx, ZP_EINVAL, "a kernel skipped unit %d: %s", unit, reason >= 1 && reason <= 6 ? names[reason] : names[0]);
+                                  "query slot out of range", "block id out of range", "keep_idx not ascending or out of range",
+                                  "wait for the unit's other workgroups expired"};
+    return fail(ctx, reason == 7 ? ZP_EHIP : ZP_EINVAL, "a kernel skipped unit %d: %s", unit, reason >= 1 && reason <= 7 ? names[reason] : names[0]);
 }
 
 extern "C" zp_status zp_validate_batch(zp_ctx *ctx, const zp_pool *p, const zp_batch *b) {

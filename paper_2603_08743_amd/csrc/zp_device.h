@@ -4,6 +4,10 @@
 #pragma once
 #include "zp_kernels.h"
 
+#ifndef ZP_COMPACT_U
+#define ZP_COMPACT_U 8
+#endif
+
 namespace zp {
 
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
@@ -41,10 +45,9 @@ __device__ __forceinline__ void report_bad(const Args &a, int unit, int reason) 
     }
 }
 
-// Decode the unit, check its metadata, stage both block tables in LDS.
-// Returns false (for every thread alike) when the unit must be skipped.
-__device__ inline bool unit_setup(const Args &a, int unit, Unit &u, int *tbl, int *dst, Misc *misc) {
-    const int tid = threadIdx.x, nt = blockDim.x;
+// Decode the unit and check its scalar metadata (identical for every thread and every workgroup
+// that looks at the unit).  Returns 0 or the reason the unit must be skipped.
+__device__ inline int unit_scalars(const Args &a, int unit, Unit &u) {
     u.unit = unit;
     u.h = unit % a.h_kv;
     u.ls = (unit / a.h_kv) % a.L_slab;
@@ -52,31 +55,37 @@ __device__ inline bool unit_setup(const Args &a, int unit, Unit &u, int *tbl, in
     u.N = a.num_blocks[u.n];
     u.T = u.N * a.b;
     u.slot = 0;
-    int bad = 0;
-    if (u.N < a.N_max || u.N > a.max_blocks) bad = BAD_NUM_BLOCKS;
-    const int idx = (u.n * a.L + a.layer0 + u.ls) * a.h_kv + u.h;
+    u.k = a.budget;
     u.vl = (u.N - 1) * a.b;
-    if (!bad && a.valid_len) {
+    u.Tv = u.vl + a.b;
+    if (u.N < a.N_max || u.N > a.max_blocks) return BAD_NUM_BLOCKS;
+    const int idx = (u.n * a.L + a.layer0 + u.ls) * a.h_kv + u.h;
+    if (a.valid_len) {
         u.vl = a.valid_len[idx];
-        if (u.vl < 0 || u.vl > (u.N - 1) * a.b) bad = BAD_VALID_LEN;
+        if (u.vl < 0 || u.vl > (u.N - 1) * a.b) return BAD_VALID_LEN;
     }
     u.Tv = u.vl + a.b;
-    if (!bad && u.Tv < a.w) bad = BAD_VALID_LEN;
-    u.k = a.budget;
-    if (!bad) {
-        if (a.stages & STAGE_LOAD_LIST) {
-            u.k = a.len_in[unit];
-            if (u.k > a.budget) bad = BAD_KEEP;
-        } else {
-            if (a.keep) u.k = a.keep[idx];
-            const int cap = a.budget < u.Tv ? a.budget : u.Tv;
-            if (u.k < a.w || u.k > cap) bad = BAD_KEEP;
-        }
+    if (u.Tv < a.w) return BAD_VALID_LEN;
+    if (a.stages & STAGE_LOAD_LIST) {
+        u.k = a.len_in[unit];
+        if (u.k > a.budget) return BAD_KEEP;
+    } else {
+        if (a.keep) u.k = a.keep[idx];
+        const int cap = a.budget < u.Tv ? a.budget : u.Tv;
+        if (u.k < a.w || u.k > cap) return BAD_KEEP;
     }
-    if (!bad && (a.stages & STAGE_SCORE)) {
+    if (a.stages & STAGE_SCORE) {
         u.slot = a.q_slot[u.n];
-        if (u.slot < 0 || u.slot >= a.M) bad = BAD_SLOT;
+        if (u.slot < 0 || u.slot >= a.M) return BAD_SLOT;
     }
+    return 0;
+}
+
+// Decode the unit, check its metadata, stage both block tables in LDS.
+// Returns false (for every thread alike) when the unit must be skipped.
+__device__ inline bool unit_setup(const Args &a, int unit, Unit &u, int *tbl, int *dst, Misc *misc) {
+    const int tid = threadIdx.x, nt = blockDim.x;
+    int bad = unit_scalars(a, unit, u);
     if (tid == 0) misc->bad = bad;
     __syncthreads();
     if (!bad) {
@@ -199,44 +208,67 @@ __device__ inline void select_unit(const Args &a, const Unit &u, unsigned *keys,
 // Compaction (appendix "KV Cache Compression"): row r of the targets <- source row list[r], K and V.
 // Safe in place: kept positions ascend, so list[r] >= r; ranks are taken in ascending chunks, every
 // row of a chunk is in registers (loads complete) before the barrier that precedes the chunk's
-// stores, and a later chunk only reads positions at or beyond its own ranks.
+// stores, and a later chunk only reads positions at or beyond its own ranks, so its loads may be in
+// flight while the previous chunk is being stored (two register sets, loads and stores overlap).
+template <int U> struct RowSet {
+    u32x4 kk[U], vv[U];
+    size_t dof[U];
+    bool mv[U];
+};
+
+template <int U>
+__device__ __forceinline__ void rows_load(const Args &a, const Unit &u, const int *tbl, const int *dst, const int *list, int k,
+                                          int r0, int rpp, int rsub, int ch, bool active, RowSet<U> &s) {
+#pragma unroll
+    for (int i = 0; i < U; i++) {
+        const int r = r0 + i * rpp + rsub;
+        s.mv[i] = false;
+        if (active && r < k) {
+            const int t = list[r];
+            const int sb = div_b(a, t), db = div_b(a, r);
+            const size_t so = row_off(a, u.ls, tbl[sb], t - sb * a.b, u.h) + ch;
+            s.dof[i] = row_off(a, u.ls, dst[db], r - db * a.b, u.h) + ch;
+            if (so != s.dof[i]) {
+                s.mv[i] = true;
+                s.kk[i] = *(const u32x4 *)(a.k + so);
+                s.vv[i] = *(const u32x4 *)(a.v + so);
+            }
+        }
+    }
+}
+
+template <int U>
+__device__ __forceinline__ void rows_store(const Args &a, const RowSet<U> &s) {
+#pragma unroll
+    for (int i = 0; i < U; i++) {
+        if (s.mv[i]) {
+            *(u32x4 *)(a.k + s.dof[i]) = s.kk[i];
+            *(u32x4 *)(a.v + s.dof[i]) = s.vv[i];
+        }
+    }
+}
+
 __device__ inline void compact_unit(const Args &a, const Unit &u, const int *tbl, const int *dst, const int *list, int k) {
     const int tid = threadIdx.x;
     const int cpr = a.row_bytes >> 4;                            // 16-byte pieces per row
     const int rpp = blockDim.x / cpr;                            // rows per pass
     const int rsub = tid / cpr, ch = (tid - rsub * cpr) << 4;
     const bool active = rsub < rpp;
-    constexpr int U = 4;
+    constexpr int U = ZP_COMPACT_U;
+    const int CH = U * rpp;                                      // rows per chunk
+    RowSet<U> A, B;
+    if (k > 0) rows_load<U>(a, u, tbl, dst, list, k, 0, rpp, rsub, ch, active, A);
 #pragma unroll 1
-    for (int r0 = 0; r0 < k; r0 += U * rpp) {
-        u32x4 kk[U], vv[U];
-        size_t dof[U];
-        bool mv[U];
-#pragma unroll
-        for (int i = 0; i < U; i++) {
-            const int r = r0 + i * rpp + rsub;
-            mv[i] = false;
-            if (active && r < k) {
-                const int t = list[r];
-                const int sb = div_b(a, t), db = div_b(a, r);
-                const size_t so = row_off(a, u.ls, tbl[sb], t - sb * a.b, u.h) + ch;
-                dof[i] = row_off(a, u.ls, dst[db], r - db * a.b, u.h) + ch;
-                if (so != dof[i]) {
-                    mv[i] = true;
-                    kk[i] = *(const u32x4 *)(a.k + so);
-                    vv[i] = *(const u32x4 *)(a.v + so);
-                }
-            }
-        }
+    for (int r0 = 0; r0 < k; r0 += 2 * CH) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-#pragma unroll
-        for (int i = 0; i < U; i++) {
-            if (mv[i]) {
-                *(u32x4 *)(a.k + dof[i]) = kk[i];
-                *(u32x4 *)(a.v + dof[i]) = vv[i];
-            }
-        }
+        if (r0 + CH < k) rows_load<U>(a, u, tbl, dst, list, k, r0 + CH, rpp, rsub, ch, active, B);
+        rows_store<U>(a, A);
+        if (r0 + CH >= k) break;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (r0 + 2 * CH < k) rows_load<U>(a, u, tbl, dst, list, k, r0 + 2 * CH, rpp, rsub, ch, active, A);
+        rows_store<U>(a, B);
     }
 }
 

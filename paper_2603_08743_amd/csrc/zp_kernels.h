@@ -16,7 +16,7 @@ enum : int {
 
 // Reasons a kernel skips a unit (reported through the context's status words).
 enum : int {
-    BAD_NUM_BLOCKS = 1, BAD_VALID_LEN = 2, BAD_KEEP = 3, BAD_SLOT = 4, BAD_BLOCK_ID = 5, BAD_KEEP_IDX = 6,
+    BAD_NUM_BLOCKS = 1, BAD_VALID_LEN = 2, BAD_KEEP = 3, BAD_SLOT = 4, BAD_BLOCK_ID = 5, BAD_KEEP_IDX = 6, BAD_SYNC = 7,
 };
 
 struct Args {
@@ -42,6 +42,13 @@ struct Args {
     int off_S, off_tbl, off_dst, off_misc, off_union, lds_bytes;
     // MFMA path geometry
     int NB;                                    // 32-row query blocks in use
+    // split path: C workgroups share one unit, each keeps a chunk of its keys resident in LDS
+    int C, NS, RP, spin_limit;                 // workgroups per unit, ticket streams, padded query rows, bound on the wait loop
+    int *sync;                                 // [256: one ticket per 128-byte line][units arrive1][units ready1][units arrive2], zeroed before the launch
+    float2 *partial;                           // [units][C][RP] per-chunk (max, sum) of every query row
+    float *lse_g;                              // [units][RP] combined log-sum-exp
+    float *sbuf;                               // [units][T_max] scores, gathered by the workgroup that finishes the unit
+    int off_chunk, off_part;                   // LDS offsets of the split phase (alias the tail's regions)
 };
 
 // launchers (host).  Each returns the hipError_t of the launch.
@@ -50,5 +57,9 @@ hipError_t launch_unit_generic(const Args &a, int units, hipStream_t s);
 bool mfma_path_available(const Args &a, int *NW, int *RB);
 hipError_t launch_unit_mfma(const Args &a, int units, int NW, int RB, hipStream_t s);
 size_t mfma_union_bytes(int d, int NW, int NB);
+// split path (zp_split.hip)
+constexpr int SPLIT_SUBS = 8;                  // 32-key subtiles a workgroup keeps in LDS
+hipError_t launch_unit_split(const Args &a, int units, int NW, int RB, hipStream_t s);
+hipError_t launch_zero_words(int *p, int n, hipStream_t s);
 
 }  // namespace zp

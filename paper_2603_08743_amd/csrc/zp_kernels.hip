@@ -135,7 +135,7 @@ size_t mfma_union_bytes(int d, int NW, int NB) {
 }
 
 template <int D, int RB, int NW, int GT>
-__global__ void __launch_bounds__(NW * 64) unit_mfma(const Args a) {
+__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 4 ? 2 : 1))) unit_mfma(const Args a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     int *tbl = (int *)(smem + a.off_tbl), *dst = (int *)(smem + a.off_dst);
     Misc *misc = (Misc *)(smem + a.off_misc);
@@ -175,37 +175,33 @@ __global__ void __launch_bounds__(NW * 64) unit_mfma(const Args a) {
     }
 
     const int ntiles = (u.Tv + KT - 1) / KT;
-    u32x4 stage[LPT];
-    auto gload = [&](int tile) {                              // key tile -> registers (rows past the end repeat the last key)
+    // Key tiles travel HBM -> registers -> LDS.  Two register sets alternate so that a tile is requested two
+    // iterations before it is needed (one tile of compute is shorter than the HBM latency).
+    u32x4 stA[LPT], stB[LPT];
+    auto gload = [&](int tile, u32x4 (&st)[LPT]) {            // rows past the end repeat the last key (masked later)
 #pragma unroll
         for (int i = 0; i < LPT; i++) {
             const int cidx = tid + i * NT, row = cidx / KTl::CPR, ch = cidx - row * KTl::CPR;
             int j = tile * KT + row;
             j = j < u.Tv ? j : u.Tv - 1;
             const int t = live_to_pos(u, a, j), blk = div_b(a, t);
-            stage[i] = *(const u32x4 *)(a.k + row_off(a, u.ls, tbl[blk], t - blk * a.b, u.h) + ch * 16);
+            st[i] = *(const u32x4 *)(a.k + row_off(a, u.ls, tbl[blk], t - blk * a.b, u.h) + ch * 16);
         }
     };
-    auto lstore = [&](char *buf) {
+    auto lstore = [&](char *buf, const u32x4 (&st)[LPT]) {
 #pragma unroll
         for (int i = 0; i < LPT; i++) {
             const int cidx = tid + i * NT, row = cidx / KTl::CPR, ch = cidx - row * KTl::CPR;
-            *(u32x4 *)(buf + row * KTl::ROW + ch * 16) = stage[i];
+            *(u32x4 *)(buf + row * KTl::ROW + ch * 16) = st[i];
         }
     };
+    char *buf0 = kbuf, *buf1 = kbuf + KTl::BYTES;
 
     // ---------------- sweep 1: per query row, running max and sum of exp2 over the keys it may see
     float rm[RB], rl[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; rb++) { rm[rb] = -1e30f; rl[rb] = 0.f; }
-    gload(0);
-    lstore(kbuf);
-    __syncthreads();
-#pragma unroll 1
-    for (int it = 0; it < ntiles; it++) {
-        const char *buf = kbuf + (it & 1) * KTl::BYTES;
-        if (it + 1 < ntiles) gload(it + 1);
-        const int j0 = it * KT;
+    auto sweep1_tile = [&](const char *buf, int j0) {
         const bool edge = j0 + KT > u.Tv - w;                 // tile reaches the window or the end: mask needed
 #pragma unroll
         for (int sub = 0; sub < KT / 32; sub++) {
@@ -243,7 +239,21 @@ __global__ void __launch_bounds__(NW * 64) unit_mfma(const Args a) {
                 rm[rb] = mn;
             }
         }
-        if (it + 1 < ntiles) lstore(kbuf + ((it + 1) & 1) * KTl::BYTES);
+    };
+    gload(0, stA);
+    lstore(buf0, stA);
+    if (ntiles > 1) gload(1, stA);
+    __syncthreads();
+#pragma unroll 1
+    for (int it = 0; it < ntiles; it += 2) {
+        if (it + 2 < ntiles) gload(it + 2, stB);
+        sweep1_tile(buf0, it * KT);
+        if (it + 1 < ntiles) lstore(buf1, stA);
+        __syncthreads();
+        if (it + 1 >= ntiles) break;
+        if (it + 3 < ntiles) gload(it + 3, stA);
+        sweep1_tile(buf1, (it + 1) * KT);
+        if (it + 2 < ntiles) lstore(buf0, stB);
         __syncthreads();
     }
 #pragma unroll
@@ -265,15 +275,7 @@ __global__ void __launch_bounds__(NW * 64) unit_mfma(const Args a) {
 #pragma unroll
         for (int i = 0; i < 16; i++) lr[rb][i] = lse[gb * 32 + 4 * hf + 8 * (i >> 2) + (i & 3)];
     }
-    gload(0);
-    lstore(kbuf);
-    __syncthreads();
-#pragma unroll 1
-    for (int it = 0; it < ntiles; it++) {
-        const char *buf = kbuf + (it & 1) * KTl::BYTES;
-        float *pt = part + (it & 1) * NW * KT;
-        if (it + 1 < ntiles) gload(it + 1);
-        const int j0 = it * KT;
+    auto sweep2_tile = [&](const char *buf, float *pt, int j0) {
         const bool edge = j0 + KT > u.Tv - w;
 #pragma unroll
         for (int sub = 0; sub < KT / 32; sub++) {
@@ -321,9 +323,9 @@ __global__ void __launch_bounds__(NW * 64) unit_mfma(const Args a) {
             ps += __shfl_xor(ps, 32);
             if (hf == 0) pt[wv * KT + sub * 32 + l32] = ps;
         }
-        if (it + 1 < ntiles) lstore(kbuf + ((it + 1) & 1) * KTl::BYTES);
-        __syncthreads();
-        if (tid < KT) {                                       // fixed-order sum over the waves: deterministic
+    };
+    auto reduce_tile = [&](const float *pt, int j0) {         // fixed-order sum over the waves: deterministic
+        if (tid < KT) {
             const int jj = j0 + tid;
             if (jj < u.Tv) {
                 float s = 0.f;
@@ -332,6 +334,25 @@ __global__ void __launch_bounds__(NW * 64) unit_mfma(const Args a) {
                 S[live_to_pos(u, a, jj)] = s / (float)w;
             }
         }
+    };
+    float *pt0 = part, *pt1 = part + NW * KT;
+    gload(0, stA);
+    lstore(buf0, stA);
+    if (ntiles > 1) gload(1, stA);
+    __syncthreads();
+#pragma unroll 1
+    for (int it = 0; it < ntiles; it += 2) {
+        if (it + 2 < ntiles) gload(it + 2, stB);
+        sweep2_tile(buf0, pt0, it * KT);
+        if (it + 1 < ntiles) lstore(buf1, stA);
+        __syncthreads();
+        reduce_tile(pt0, it * KT);
+        if (it + 1 >= ntiles) break;
+        if (it + 3 < ntiles) gload(it + 3, stA);
+        sweep2_tile(buf1, pt1, (it + 1) * KT);
+        if (it + 2 < ntiles) lstore(buf0, stB);
+        __syncthreads();
+        reduce_tile(pt1, (it + 1) * KT);
     }
     __syncthreads();
     unit_tail(a, u, smem, tbl, dst, misc);

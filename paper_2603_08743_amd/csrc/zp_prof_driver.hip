@@ -1,5 +1,5 @@
 // Stand-alone driver for hardware-counter runs of the fused compression kernel (no Python, no torch):
-//   rocprofv3 --pmc FETCH_SIZE -- ./zp_prof_driver [B] [L_slab] [config] [reps] [stages]
+//   rocprofv3 --pmc FETCH_SIZE -- ./zp_prof_driver [B] [L_slab] [config] [reps] [stages] [split] [streams]
 // stages = 1 also times the staged calls (zp_score, zp_select_topk, zp_compact_kv) one by one.
 // It builds one layer slab of a benchmark-shaped workload with an on-device integer-hash fill
 // (approximately N(0,1) values, 5 % of the key positions scaled x3, shuffled block tables, per-head
@@ -57,6 +57,8 @@ int main(int argc, char **argv) {
     const int cfg = argc > 3 ? atoi(argv[3]) : 2;
     const int reps = argc > 4 ? atoi(argv[4]) : 1;
     const int staged = argc > 5 ? atoi(argv[5]) : 0;
+    const int split = argc > 6 ? atoi(argv[6]) : -1;
+    const int streams = argc > 7 ? atoi(argv[7]) : 8;
     int h_kv = 8, h_q = 32, d = 128, b = 16, N_max = 257, w = 64;
     bool per_head_keep = true;
     if (cfg == 1) { h_kv = 4; h_q = 28; N_max = 129; w = 32; per_head_keep = false; }
@@ -97,6 +99,8 @@ int main(int argc, char **argv) {
 
     zp_ctx *ctx;
     if (zp_create(&ctx) != ZP_OK) { fprintf(stderr, "%s\n", zp_last_error(nullptr)); return 1; }
+    zp_set_option(ctx, ZP_OPT_SPLIT, split);
+    zp_set_option(ctx, ZP_OPT_STREAMS, streams);
     zp_pool pool = {K, V, Q, 0, Ls, N_total, b, h_kv, h_q, d, B, w, ZP_BF16};
     zp_batch batch = {B, N_max, N_max, Ls, d_tbl, nullptr, d_nb, d_slot, nullptr, d_keep};
     hipEvent_t e0, e1;
@@ -144,8 +148,8 @@ int main(int argc, char **argv) {
     }
     long long kept = 0;
     for (int x : keep) kept += x;
-    printf("cfg %d: B=%d L_slab=%d units=%d  zp_compress %.3f ms/launch over %d launch(es); plain_copy moves %zu bytes each way; kept rows %lld\n",
-           cfg, B, Ls, B * Ls * h_kv, total_ms / reps, reps, kv_elems * 2, kept);
+    printf("cfg %d split=%d streams=%d: B=%d L_slab=%d units=%d  zp_compress %.3f ms/launch over %d launch(es); plain_copy moves %zu bytes each way; kept rows %lld\n",
+           cfg, split, streams, B, Ls, B * Ls * h_kv, total_ms / reps, reps, kv_elems * 2, kept);
     zp_destroy(ctx);
     return 0;
 }

@@ -11,6 +11,14 @@ from tests.util import random_problem
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True, params=[1, 0], ids=["split", "single"])
+def split_mode(request):
+    """Every case runs on both bf16 kernels: several workgroups per unit and one per unit."""
+    G.ctx().zp_set_option(binding.ZP_OPT_SPLIT, request.param)
+    yield request.param
+    G.ctx().zp_set_option(binding.ZP_OPT_SPLIT, -1)
+
+
 def test_config0_tiny_fp32_exact():
     w = workloads.config(0)
     p, pool, batch = G.workload_problem(w)
