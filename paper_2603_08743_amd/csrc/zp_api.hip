@@ -122,6 +122,7 @@ static zp_status prepare(zp_ctx *ctx, const char *who, const zp_pool *p, const z
     if (row_bytes % 16 || row_bytes > 1024) return fail(ctx, ZP_EUNSUPPORTED, "%s: row of %lld bytes (need a multiple of 16, at most 1024)", who, row_bytes);
     const long long T_max = (long long)b->max_blocks * p->b, budget = (long long)(b->N_max - 1) * p->b;
     if (budget < p->w) return fail(ctx, ZP_EINVAL, "%s: budget %lld smaller than the window %d", who, budget, p->w);
+    if ((long long)p->N_total * p->b > 0x7fffffffLL) return fail(ctx, ZP_EUNSUPPORTED, "%s: N_total*b exceeds 2^31-1 token slots per layer", who);
     if (T_max > 65535) return fail(ctx, ZP_EUNSUPPORTED, "%s: %lld positions per request exceed 65535", who, T_max);
     const long long units = (long long)b->B * p->L_slab * p->h_kv;
     if (units > 0x7fffffffLL) return fail(ctx, ZP_EUNSUPPORTED, "%s: too many units", who);

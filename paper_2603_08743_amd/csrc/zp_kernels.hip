@@ -12,6 +12,8 @@
 // the logits and reduces them to S[t] = (1/w) sum_u max_g exp(a[g,u,t] - lse[g,u]).
 #include "zp_device.h"
 
+#include <type_traits>
+
 namespace zp {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -178,44 +180,59 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW
     // Key tiles travel HBM -> registers -> LDS.  Two register sets alternate so that a tile is requested two
     // iterations before it is needed (one tile of compute is shorter than the HBM latency).
     u32x4 stA[LPT], stB[LPT];
+    // a thread always fetches the same 16-byte piece of rows r0, r0 + RSTEP, ...: one 64-bit base, then
+    // base + token * (bytes between consecutive tokens) with token = block * b + slot (fits 32 bits, host-checked)
+    constexpr int RSTEP = NT / KTl::CPR;
+    const int r0 = tid / KTl::CPR;
+    const char *kbase = a.k + ((size_t)u.ls * a.N_total * a.b * a.h_kv + u.h) * (size_t)(D * 2) + (tid - r0 * KTl::CPR) * 16;
+    const unsigned tok_bytes = (unsigned)a.h_kv * (D * 2);
+    const int gap = (u.N - 1) * a.b - u.vl;                   // stale positions between the live prefix and the last block
     auto gload = [&](int tile, u32x4 (&st)[LPT]) {            // rows past the end repeat the last key (masked later)
 #pragma unroll
         for (int i = 0; i < LPT; i++) {
-            const int cidx = tid + i * NT, row = cidx / KTl::CPR, ch = cidx - row * KTl::CPR;
-            int j = tile * KT + row;
+            int j = tile * KT + r0 + i * RSTEP;
             j = j < u.Tv ? j : u.Tv - 1;
-            const int t = live_to_pos(u, a, j), blk = div_b(a, t);
-            st[i] = *(const u32x4 *)(a.k + row_off(a, u.ls, tbl[blk], t - blk * a.b, u.h) + ch * 16);
+            const int t = j < u.vl ? j : j + gap;
+            unsigned tok;
+            if (a.b_shift >= 0) {
+                const int blk = t >> a.b_shift;
+                tok = ((unsigned)tbl[blk] << a.b_shift) + (unsigned)(t & (a.b - 1));
+            } else {
+                const int blk = t / a.b;
+                tok = (unsigned)tbl[blk] * (unsigned)a.b + (unsigned)(t - blk * a.b);
+            }
+            st[i] = *(const u32x4 *)(kbase + (size_t)tok * tok_bytes);
         }
     };
+    const int lds_st = r0 * KTl::ROW + (tid - r0 * KTl::CPR) * 16;
     auto lstore = [&](char *buf, const u32x4 (&st)[LPT]) {
 #pragma unroll
-        for (int i = 0; i < LPT; i++) {
-            const int cidx = tid + i * NT, row = cidx / KTl::CPR, ch = cidx - row * KTl::CPR;
-            *(u32x4 *)(buf + row * KTl::ROW + ch * 16) = st[i];
-        }
+        for (int i = 0; i < LPT; i++) *(u32x4 *)(buf + lds_st + i * RSTEP * KTl::ROW) = st[i];
     };
     char *buf0 = kbuf, *buf1 = kbuf + KTl::BYTES;
+    f32x16 zero16;
+#pragma unroll
+    for (int i = 0; i < 16; i++) zero16[i] = 0.f;
 
     // ---------------- sweep 1: per query row, running max and sum of exp2 over the keys it may see
     float rm[RB], rl[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; rb++) { rm[rb] = -1e30f; rl[rb] = 0.f; }
-    auto sweep1_tile = [&](const char *buf, int j0) {
-        const bool edge = j0 + KT > u.Tv - w;                 // tile reaches the window or the end: mask needed
+    // The sum of exp2(x - ref) is kept against a per-row reference `rm` that only moves when the sum leaves the
+    // safe range (first subtile, or logits that jump by more than ~2^100): then the subtile is redone with the
+    // proper maximum.  This keeps the common path free of the max reduction: fma, exp2, add per logit.
+    auto sweep1_body = [&](const char *buf, int j0, auto edge_tag) {
+        constexpr bool edge = decltype(edge_tag)::value;
 #pragma unroll
         for (int sub = 0; sub < KT / 32; sub++) {
             f32x16 acc[RB];
-#pragma unroll
-            for (int rb = 0; rb < RB; rb++)
-#pragma unroll
-                for (int i = 0; i < 16; i++) acc[rb][i] = 0.f;
             const char *kp = buf + (sub * 32 + l32) * KTl::ROW + hf * 16;
 #pragma unroll
             for (int kk = 0; kk < KK; kk++) {
                 const bf16x8 kf = *(const bf16x8 *)(kp + kk * 32);
 #pragma unroll
-                for (int rb = 0; rb < RB; rb++) acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rb][kk], acc[rb], 0, 0, 0);
+                for (int rb = 0; rb < RB; rb++)
+                    acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rb][kk], kk ? acc[rb] : zero16, 0, 0, 0);
             }
             // acc[rb][i]: key j0 + sub*32 + 4*hf + 8*(i/4) + i%4, query row = this lane's column
 #pragma unroll
@@ -228,17 +245,29 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW
                         if (j > lim) acc[rb][i] = -INFINITY;
                     }
                 }
-                float tm = acc[rb][0];
-#pragma unroll
-                for (int i = 1; i < 16; i++) tm = fmaxf(tm, acc[rb][i]);
-                const float mn = fmaxf(rm[rb], tm * c);
                 float sum = 0.f;
 #pragma unroll
-                for (int i = 0; i < 16; i++) sum += fexp2(fmaf(acc[rb][i], c, -mn));
-                rl[rb] = rl[rb] * fexp2(rm[rb] - mn) + sum;
-                rm[rb] = mn;
+                for (int i = 0; i < 16; i++) sum += fexp2(fmaf(acc[rb][i], c, -rm[rb]));
+                const float ln = rl[rb] + sum;
+                if (__builtin_expect(__any(!(ln < 1e30f)), 0)) {        // wave-uniform, rare
+                    float tm = acc[rb][0];
+#pragma unroll
+                    for (int i = 1; i < 16; i++) tm = fmaxf(tm, acc[rb][i]);
+                    const float mn = fmaxf(rm[rb], tm * c);
+                    sum = 0.f;
+#pragma unroll
+                    for (int i = 0; i < 16; i++) sum += fexp2(fmaf(acc[rb][i], c, -mn));
+                    rl[rb] = rl[rb] * fexp2(rm[rb] - mn) + sum;
+                    rm[rb] = mn;
+                } else {
+                    rl[rb] = ln;
+                }
             }
         }
+    };
+    auto sweep1_tile = [&](const char *buf, int j0) {
+        if (j0 + KT > u.Tv - w) sweep1_body(buf, j0, std::true_type());
+        else sweep1_body(buf, j0, std::false_type());
     };
     gload(0, stA);
     lstore(buf0, stA);
@@ -275,21 +304,20 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW
 #pragma unroll
         for (int i = 0; i < 16; i++) lr[rb][i] = lse[gb * 32 + 4 * hf + 8 * (i >> 2) + (i & 3)];
     }
-    auto sweep2_tile = [&](const char *buf, float *pt, int j0) {
-        const bool edge = j0 + KT > u.Tv - w;
+    // max_g exp2(x_g - lse_g) = exp2(max_g (x_g - lse_g)): the maximum over the group is taken before the
+    // exponential, so a window row costs one exp2 instead of G.
+    auto sweep2_body = [&](const char *buf, float *pt, int j0, auto edge_tag) {
+        constexpr bool edge = decltype(edge_tag)::value;
 #pragma unroll
         for (int sub = 0; sub < KT / 32; sub++) {
             f32x16 acc[RB];
-#pragma unroll
-            for (int rb = 0; rb < RB; rb++)
-#pragma unroll
-                for (int i = 0; i < 16; i++) acc[rb][i] = 0.f;
             const char *kp = buf + (sub * 32 + l32) * KTl::ROW + hf * 16;
 #pragma unroll
             for (int kk = 0; kk < KK; kk++) {
                 const bf16x8 kf = *(const bf16x8 *)(kp + kk * 32);
 #pragma unroll
-                for (int rb = 0; rb < RB; rb++) acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][kk], kf, acc[rb], 0, 0, 0);
+                for (int rb = 0; rb < RB; rb++)
+                    acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][kk], kf, kk ? acc[rb] : zero16, 0, 0, 0);
             }
             // acc[rb][i]: slot i of this half-wave, key j = j0 + sub*32 + l32
             const int j = j0 + sub * 32 + l32;
@@ -297,32 +325,36 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW
             float ps = 0.f;
 #pragma unroll
             for (int rb = 0; rb < RB; rb++) {
-                float p[16];
+                float y[16];                                  // x - lse in base 2; zero rows have lse = +inf: y = -inf
 #pragma unroll
-                for (int i = 0; i < 16; i++) p[i] = fexp2(fmaf(acc[rb][i], c, -lr[rb][i]));
+                for (int i = 0; i < 16; i++) y[i] = fmaf(acc[rb][i], c, -lr[rb][i]);
                 if (GT) {
 #pragma unroll
                     for (int ul = 0; ul < (GT ? 16 / GT : 1); ul++) {
-                        float mx = p[ul * GT];
+                        float mx = y[ul * GT];
 #pragma unroll
-                        for (int g = 1; g < GT; g++) mx = fmaxf(mx, p[ul * GT + g]);
-                        if (edge && ub[rb] + ul < thr) mx = 0.f;
-                        ps += mx;
+                        for (int g = 1; g < GT; g++) mx = fmaxf(mx, y[ul * GT + g]);
+                        if (edge && ub[rb] + ul < thr) mx = -INFINITY;
+                        ps += fexp2(mx);
                     }
                 } else {                                      // group size known only at run time
-                    float mx = 0.f;
+                    float mx = -INFINITY;
                     int g = 0, ul = 0;
 #pragma unroll
                     for (int i = 0; i < 16; i++) {
-                        const float v = (edge && ub[rb] + ul < thr) ? 0.f : p[i];
+                        const float v = (edge && ub[rb] + ul < thr) ? -INFINITY : y[i];
                         mx = fmaxf(mx, v);
-                        if (++g == G) { ps += mx; mx = 0.f; g = 0; ul++; }
+                        if (++g == G) { ps += fexp2(mx); mx = -INFINITY; g = 0; ul++; }
                     }
                 }
             }
             ps += __shfl_xor(ps, 32);
             if (hf == 0) pt[wv * KT + sub * 32 + l32] = ps;
         }
+    };
+    auto sweep2_tile = [&](const char *buf, float *pt, int j0) {
+        if (j0 + KT > u.Tv - w) sweep2_body(buf, pt, j0, std::true_type());
+        else sweep2_body(buf, pt, j0, std::false_type());
     };
     auto reduce_tile = [&](const float *pt, int j0) {         // fixed-order sum over the waves: deterministic
         if (tid < KT) {
@@ -336,23 +368,26 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW
         }
     };
     float *pt0 = part, *pt1 = part + NW * KT;
-    gload(0, stA);
+    // tiles are taken in DESCENDING order (tile number rt = ntiles-1-it): the keys sweep 1 read last are the ones
+    // most likely to be still in L2 / Infinity Cache
+    gload(ntiles - 1, stA);
     lstore(buf0, stA);
-    if (ntiles > 1) gload(1, stA);
+    if (ntiles > 1) gload(ntiles - 2, stA);
     __syncthreads();
 #pragma unroll 1
     for (int it = 0; it < ntiles; it += 2) {
-        if (it + 2 < ntiles) gload(it + 2, stB);
-        sweep2_tile(buf0, pt0, it * KT);
+        const int rt = ntiles - 1 - it;
+        if (it + 2 < ntiles) gload(rt - 2, stB);
+        sweep2_tile(buf0, pt0, rt * KT);
         if (it + 1 < ntiles) lstore(buf1, stA);
         __syncthreads();
-        reduce_tile(pt0, it * KT);
+        reduce_tile(pt0, rt * KT);
         if (it + 1 >= ntiles) break;
-        if (it + 3 < ntiles) gload(it + 3, stA);
-        sweep2_tile(buf1, pt1, (it + 1) * KT);
+        if (it + 3 < ntiles) gload(rt - 3, stA);
+        sweep2_tile(buf1, pt1, (rt - 1) * KT);
         if (it + 2 < ntiles) lstore(buf0, stB);
         __syncthreads();
-        reduce_tile(pt1, (it + 1) * KT);
+        reduce_tile(pt1, (rt - 1) * KT);
     }
     __syncthreads();
     unit_tail(a, u, smem, tbl, dst, misc);
@@ -388,6 +423,12 @@ static hipError_t launch_g(const Args &a, int units, hipStream_t s) {
         hipLaunchKernelGGL((unit_mfma<D, RB, NW, GT>), grid, block, a.lds_bytes, s, a);      \
     }                                                                                        \
     break;
+#ifdef ZP_DEV_FAST   /* development builds: only the instantiation of the 8B-like benchmark shape */
+    switch (a.G) {
+        case 4: ZP_LAUNCH(4)
+        default: return hipErrorInvalidConfiguration;
+    }
+#else
     switch (a.G) {
         case 4: ZP_LAUNCH(4)
         case 5: ZP_LAUNCH(5)
@@ -395,12 +436,17 @@ static hipError_t launch_g(const Args &a, int units, hipStream_t s) {
         case 8: ZP_LAUNCH(8)
         default: ZP_LAUNCH(0)
     }
+#endif
 #undef ZP_LAUNCH
     return hipGetLastError();
 }
 
 template <int D>
 static hipError_t launch_d(const Args &a, int units, int NW, int RB, hipStream_t s) {
+#ifdef ZP_DEV_FAST
+    if (D == 128 && RB == 2 && NW == 4) return launch_g<D, 2, 4>(a, units, s);
+    return hipErrorInvalidConfiguration;
+#endif
     if (RB == 1 && NW == 1) return launch_g<D, 1, 1>(a, units, s);
     if (RB == 1 && NW == 2) return launch_g<D, 1, 2>(a, units, s);
     if (RB == 1 && NW == 4) return launch_g<D, 1, 4>(a, units, s);

@@ -356,6 +356,12 @@ static hipError_t launch_g(const Args &a, int units, hipStream_t s) {
         hipLaunchKernelGGL((unit_split<D, RB, NW, GT>), grid, block, a.lds_bytes, s, a);     \
     }                                                                                        \
     break;
+#ifdef ZP_DEV_FAST   /* development builds: only the instantiation of the 8B-like benchmark shape */
+    switch (a.G) {
+        case 4: ZP_LAUNCH(4)
+        default: return hipErrorInvalidConfiguration;
+    }
+#else
     switch (a.G) {
         case 4: ZP_LAUNCH(4)
         case 5: ZP_LAUNCH(5)
@@ -363,12 +369,17 @@ static hipError_t launch_g(const Args &a, int units, hipStream_t s) {
         case 8: ZP_LAUNCH(8)
         default: ZP_LAUNCH(0)
     }
+#endif
 #undef ZP_LAUNCH
     return hipGetLastError();
 }
 
 template <int D>
 static hipError_t launch_d(const Args &a, int units, int NW, int RB, hipStream_t s) {
+#ifdef ZP_DEV_FAST
+    if (D == 128 && RB == 2 && NW == 4) return launch_g<D, 2, 4>(a, units, s);
+    return hipErrorInvalidConfiguration;
+#endif
     if (RB == 1 && NW == 1) return launch_g<D, 1, 1>(a, units, s);
     if (RB == 1 && NW == 2) return launch_g<D, 1, 2>(a, units, s);
     if (RB == 1 && NW == 4) return launch_g<D, 1, 4>(a, units, s);

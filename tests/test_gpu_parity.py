@@ -117,3 +117,17 @@ def test_duplicate_keys_tie_break_end_to_end():
     assert len({sh[t].tobytes() for t in (5, 19, 21, 22, 40, 41, 57)}) == 1
     o_idx, _ = oracle.select(p, s.cpu().numpy())
     assert np.array_equal(o_idx, idx.cpu().numpy())
+
+
+def test_logit_spike_late_in_the_sequence():
+    # one late key is a large multiple of a window query: its logit exceeds everything before it by hundreds of
+    # binary orders of magnitude, which forces the running softmax reference of sweep 1 to be re-based mid-sequence
+    from tests.util import bf16_bits_to_f32, f32_to_bf16_bits
+    p = random_problem(500, B=1, L=1, h_kv=2, G=4, d=128, b=16, N_max=40, w=16, bf16=True)
+    tbl = p.block_table[0]
+    for h, t in ((0, 300), (1, 37)):
+        q = bf16_bits_to_f32(p.Q[0, p.q_slot[0], 5, h * 4 + 1])
+        p.K[0, tbl[t // 16], t % 16, h] = f32_to_bf16_bits(30.0 * q)
+    pool, batch = G.to_device(p)
+    rep = G.full_protocol(p, pool, batch)
+    assert rep["worst_rel"] < 1e-3
