@@ -21,6 +21,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes of one launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in
+# profiles/unit_mfma_cfg2_hbm_traffic.md (scaled by the plain-copy calibration); keyed by (config, B, layers per launch)
+MEASURED_TRAFFIC = {(2, 256, 8): 78.43e9}
 
 
 def log(msg):
@@ -181,7 +184,7 @@ def main():
         "request_tokens_per_s": req_tokens_step / (ms_per_step * 1e-3),
         "wall_ms_per_step_incl_restore": wall * 1e3 / args.steps,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None, "kernel": "zp::unit_mfma (fused zp_compress)", "ms_per_launch": ms_per_launch,
+                     "traffic": MEASURED_TRAFFIC.get((args.config, w.B, Ls)), "kernel": "zp::unit_mfma (fused zp_compress)", "ms_per_launch": ms_per_launch,
                      "algorithmic_bytes_per_launch": bytes_launch, "moved_rows_per_launch": moved, "kept_rows_per_launch": kept},
         "cpu_baseline": cpu,
         "context": "paper: >2.1x end-to-end TPS over a Full-KV engine at ~95% accuracy, Qwen3-8B, AMC 23, budget 2048, one NVIDIA A100 (not comparable; no isolated number for this step is published)",
