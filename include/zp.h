@@ -153,6 +153,18 @@ zp_status zp_compress(zp_ctx *ctx, const zp_pool *pool, const zp_batch *batch, i
    last call skipped a unit (ZP_EINVAL, with the first offending unit in the error text). */
 zp_status zp_sync_status(zp_ctx *ctx, void *stream);
 
+/*
+ * Check-only helper, NOT part of the compression path and not tuned: paged decode attention over a
+ * (compacted) cache with per-head lengths, so that a caller can verify that the compacted cache is usable
+ * (textbook softmax(q K^T / sqrt d) V; the paper's engine uses its own attention kernels for decoding).
+ * pool: k, v and the shape fields are used (q, M, w ignored).  table: [dev] int32 [B][table_stride] logical ->
+ * physical block; len: [dev] int32 [B][L_slab][h_kv] rows to attend to (<= table_stride*b);
+ * q: [dev] [B][L_slab][h_q][d] in the pool's dtype; out: [dev] fp32 [B][L_slab][h_q][d] (zeros where len = 0).
+ * Bad table entries or lengths are reported through zp_sync_status().
+ */
+zp_status zp_decode_attention(zp_ctx *ctx, const zp_pool *pool, int32_t B, int32_t table_stride, const int32_t *table,
+                              const int32_t *len, const void *q, float *out, void *stream);
+
 /* Synchronous, slow, complete check of a batch: copies the tables to the host and
    verifies every rule stated in zp_batch.  ZP_OK or ZP_EINVAL with a message. */
 zp_status zp_validate_batch(zp_ctx *ctx, const zp_pool *pool, const zp_batch *batch);

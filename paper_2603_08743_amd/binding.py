@@ -21,7 +21,7 @@ ZP_F32, ZP_BF16 = 0, 1
 ZP_OPT_SPLIT, ZP_OPT_SPIN_LIMIT, ZP_OPT_STREAMS = 1, 2, 3
 
 EXPORTS = ("zp_create", "zp_destroy", "zp_last_error", "zp_scratch_bytes", "zp_score", "zp_select_topk", "zp_compact_kv",
-           "zp_compress", "zp_sync_status", "zp_validate_batch", "zp_plan", "zp_set_option")
+           "zp_compress", "zp_sync_status", "zp_validate_batch", "zp_plan", "zp_set_option", "zp_decode_attention")
 
 
 class ZpError(RuntimeError):
@@ -173,6 +173,17 @@ class Context:
         self._check(self.lib.zp_compress(self.h, ctypes.byref(p), ctypes.byref(b), ctypes.c_void_p(len_out.data_ptr()),
                                          ctypes.c_void_p(scores_dbg.data_ptr() if scores_dbg is not None else None),
                                          ctypes.c_void_p(keep_idx_dbg.data_ptr() if keep_idx_dbg is not None else None), _stream()))
+
+    def zp_decode_attention(self, pool: Pool, table: torch.Tensor, length: torch.Tensor, q: torch.Tensor, out: torch.Tensor) -> None:
+        """Check-only paged decode attention; q [B, L_slab, h_q, d] (pool dtype), out fp32 of the same shape."""
+        p = pool.c()
+        B, stride = table.shape
+        assert q.is_cuda and q.is_contiguous() and q.dtype == pool.k.dtype and tuple(q.shape) == (B, p.L_slab, p.h_q, p.d)
+        assert out.is_cuda and out.is_contiguous() and out.dtype == torch.float32 and out.shape == q.shape
+        assert length.numel() == B * p.L_slab * p.h_kv
+        self._check(self.lib.zp_decode_attention(self.h, ctypes.byref(p), ctypes.c_int32(B), ctypes.c_int32(stride),
+                                                 ctypes.c_void_p(_i32ptr(table)), ctypes.c_void_p(_i32ptr(length)),
+                                                 ctypes.c_void_p(q.data_ptr()), ctypes.c_void_p(out.data_ptr()), _stream()))
 
     def zp_set_option(self, option: int, value: int) -> None:
         self._check(self.lib.zp_set_option(self.h, ctypes.c_int32(option), ctypes.c_int32(value)))

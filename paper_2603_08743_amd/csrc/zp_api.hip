@@ -272,6 +272,29 @@ extern "C" zp_status zp_compress(zp_ctx *ctx, const zp_pool *pool, const zp_batc
     return launch(ctx, "zp_compress", a, path, NW, RB, stream);
 }
 
+extern "C" zp_status zp_decode_attention(zp_ctx *ctx, const zp_pool *p, int32_t B, int32_t table_stride, const int32_t *table,
+                                         const int32_t *len, const void *q, float *out, void *stream) {
+    if (!ctx) return fail(nullptr, ZP_EINVAL, "zp_decode_attention: ctx is NULL");
+    if (!p || !p->k || !p->v) return fail(ctx, ZP_EINVAL, "zp_decode_attention: pool is NULL");
+    if (p->dtype != ZP_F32 && p->dtype != ZP_BF16) return fail(ctx, ZP_EINVAL, "zp_decode_attention: unknown dtype %d", p->dtype);
+    if (B < 0 || table_stride <= 0 || p->L_slab <= 0 || p->N_total <= 0 || p->b <= 0 || p->h_kv <= 0 || p->h_q <= 0 || p->d <= 0)
+        return fail(ctx, ZP_EINVAL, "zp_decode_attention: dimensions must be positive");
+    if (p->h_q % p->h_kv) return fail(ctx, ZP_EUNSUPPORTED, "zp_decode_attention: h_q %d is not a multiple of h_kv %d", p->h_q, p->h_kv);
+    if (p->d > 256) return fail(ctx, ZP_EUNSUPPORTED, "zp_decode_attention: head dimension %d above 256", p->d);
+    if (B > 0 && (!table || !len || !q || !out)) return fail(ctx, ZP_EINVAL, "zp_decode_attention: NULL argument");
+    const long long items = (long long)B * p->L_slab * p->h_q;
+    if (items > 0x7fffffffLL) return fail(ctx, ZP_EUNSUPPORTED, "zp_decode_attention: too many queries");
+    zp::DecodeArgs a;
+    a.k = (const char *)p->k; a.v = (const char *)p->v; a.q = (const char *)q; a.out = out; a.table = table; a.len = len;
+    a.status = ctx->d_status;
+    a.B = B; a.L_slab = p->L_slab; a.N_total = p->N_total; a.b = p->b; a.h_kv = p->h_kv; a.h_q = p->h_q; a.d = p->d;
+    a.dtype = p->dtype; a.table_stride = table_stride; a.row_bytes = p->d * (p->dtype == ZP_F32 ? 4 : 2);
+    a.scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)p->d));
+    hipError_t e = zp::launch_decode_attention(a, (int)items, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(ctx, ZP_EHIP, "zp_decode_attention: kernel launch failed: %s", hipGetErrorString(e));
+    return ZP_OK;
+}
+
 extern "C" zp_status zp_sync_status(zp_ctx *ctx, void *stream) {
     if (!ctx) return fail(nullptr, ZP_EINVAL, "zp_sync_status: ctx is NULL");
     hipStream_t s = (hipStream_t)stream;

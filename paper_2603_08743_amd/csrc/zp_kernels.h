@@ -51,6 +51,17 @@ struct Args {
     int off_chunk, off_part;                   // LDS offsets of the split phase (alias the tail's regions)
 };
 
+// check-only paged decode attention (zp_check.hip)
+struct DecodeArgs {
+    const char *k, *v, *q;      // pools [L_slab][N_total][b][h_kv][d]; q [B][L_slab][h_q][d]
+    float *out;                 // [B][L_slab][h_q][d]
+    const int *table, *len;     // [B][table_stride], [B][L_slab][h_kv]
+    int *status;
+    int B, L_slab, N_total, b, h_kv, h_q, d, dtype, table_stride, row_bytes;
+    float scale_log2;
+};
+hipError_t launch_decode_attention(const DecodeArgs &a, int items, hipStream_t s);
+
 // launchers (host).  Each returns the hipError_t of the launch.
 hipError_t launch_unit_generic(const Args &a, int units, hipStream_t s);
 // returns hipErrorInvalidConfiguration when no MFMA instantiation covers (d, G, w)
