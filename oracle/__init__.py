@@ -54,7 +54,7 @@ def _load():
     global _lib
     if _lib is None:
         _lib = ctypes.CDLL(build())
-        for name in ("zo_score", "zo_select", "zo_compact", "zo_plan", "zo_decode_attention", "zo_threads"):
+        for name in ("zo_score", "zo_select", "zo_compact", "zo_plan", "zo_decode_attention", "zo_threads", "zo_score_ex", "zo_compact_global"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -126,6 +126,47 @@ def score(p: Problem) -> np.ndarray:
     _check(_load().zo_score(ctypes.byref(sh), ctypes.byref(bt), ctypes.c_void_p(p.K.ctypes.data),
                             ctypes.c_void_p(p.Q.ctypes.data), ctypes.c_void_p(out.ctypes.data)), "score")
     return out
+
+
+class _Extras(ctypes.Structure):
+    _fields_ = [("F", ctypes.c_void_p), ("compressed", ctypes.c_void_p), ("alpha", ctypes.c_double), ("pool_kernel", ctypes.c_int32),
+                ("lam", ctypes.c_double), ("tau", ctypes.c_double), ("p", ctypes.c_double)]
+
+
+@dataclass
+class Extras:
+    """Score refinements: global score (cache F, updated in place), max pooling, lightning redundancy."""
+    F: Optional[np.ndarray] = None            # [L, N_total, b, h_kv] float32
+    compressed: Optional[np.ndarray] = None   # [B] int32, nonzero = the request was compressed before
+    alpha: float = 0.8
+    pool_kernel: int = 1
+    lam: float = 0.0
+    tau: float = 1.0
+    p: float = 1.0
+
+
+def score_ex(p: Problem, ex: Extras) -> np.ndarray:
+    """Attention score followed by global score, pooling and S - lambda R (fp64); ex.F is updated in place."""
+    sh, bt, keepalive = _structs(p)
+    L, _, b, h_kv = p.K.shape[:4]
+    if ex.F is not None:
+        assert ex.F.dtype == np.float32 and ex.F.flags.c_contiguous and ex.F.shape == p.K.shape[:4]
+    comp = _i32(ex.compressed)
+    cx = _Extras(_ptr(ex.F), _ptr(comp), ex.alpha, ex.pool_kernel, ex.lam, ex.tau, ex.p)
+    out = np.empty((bt.B, L, h_kv, bt.max_blocks * b), dtype=np.float64)
+    _check(_load().zo_score_ex(ctypes.byref(sh), ctypes.byref(bt), ctypes.c_void_p(p.K.ctypes.data), ctypes.c_void_p(p.Q.ctypes.data),
+                               ctypes.byref(cx), ctypes.c_void_p(out.ctypes.data)), "score_ex")
+    return out
+
+
+def compact_global(p: Problem, F: np.ndarray, keep_idx: np.ndarray, ln: np.ndarray) -> None:
+    """Move the cached global scores of the kept entries into the targets, in place in F."""
+    sh, bt, keepalive = _structs(p)
+    idx = np.ascontiguousarray(keep_idx, dtype=np.int32)
+    ln = np.ascontiguousarray(ln, dtype=np.int32)
+    assert F.dtype == np.float32 and F.flags.c_contiguous and F.shape == p.K.shape[:4]
+    _check(_load().zo_compact_global(ctypes.byref(sh), ctypes.byref(bt), ctypes.c_void_p(F.ctypes.data),
+                                     ctypes.c_void_p(idx.ctypes.data), ctypes.c_void_p(ln.ctypes.data)), "compact_global")
 
 
 def select(p: Problem, scores_f32: np.ndarray):

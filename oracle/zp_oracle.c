@@ -208,6 +208,142 @@ int zo_score(const zo_shape *s, const zo_batch *bt, const void *K, const void *Q
     return failed ? ZO_ENOMEM : ZO_OK;
 }
 
+/*
+ * Score refinements the paper layers on top of the attention score, in its order (appendix "Global Score",
+ * "Pooling at the Sequence Dimension", "Redundancy Score of Key states", "Lightning Redundancy", "Combining All
+ * These Techniques"):  attention score -> global score (decayed max with the cached history) -> max pooling along
+ * the sequence -> S - lambda * R with the lightning (within-block) redundancy R.
+ * Readings (also in the design notes):
+ *  X1 History exists for the live prefix [0, valid_len) of a request that was compressed before; the last block
+ *     holds new tokens without history (the paper's "not the last block" for w <= b, stated on positions).
+ *  X2 The cache F holds fp32 values; the value stored is the score after the global update, before pooling and
+ *     redundancy (the paper pools "after computing the global score" and applies redundancy "after max pooling").
+ *  X3 MaxPool1D: odd kernel m, stride 1, implicit -inf padding (the library default the paper uses), taken along
+ *     the live sequence; the paper does not give m, so it is a parameter (1 = off).
+ *  X4 Lightning redundancy: cosine similarity between the live keys of one physical block; diagonal zeroed; in every
+ *     column the LAST (highest row, i.e. newest token) entry above the threshold p is zeroed; row sums are divided
+ *     by the live sequence length Tv, then a softmax with temperature tau over the live sequence gives R.
+ *     A key of zero norm has similarity 0 to everything.  p is a parameter (the paper gives no value).
+ */
+typedef struct {
+    float *F;                  /* [L][N_total][b][h_kv] global-score cache, updated in place; NULL = no global score */
+    const int32_t *compressed; /* [B] nonzero: the request was compressed before (history valid); NULL = none was */
+    double alpha;              /* decay of the history */
+    int32_t pool_kernel;       /* odd >= 1; 1 = no pooling */
+    double lambda, tau, p;     /* redundancy weight (0 = off), softmax temperature, similarity threshold */
+} zo_extras;
+
+static size_t f_index(const zo_shape *s, int l, int blk, int slot, int h) {
+    return (((size_t)l * s->N_total + blk) * s->b + slot) * s->h_kv + h;
+}
+
+int zo_score_ex(const zo_shape *s, const zo_batch *bt, const void *K, const void *Q, const zo_extras *ex, double *scores) {
+    int rc = zo_score(s, bt, K, Q, scores);
+    if (rc || !ex) return rc;
+    if (ex->pool_kernel < 1 || !(ex->pool_kernel & 1) || (ex->lambda != 0.0 && !(ex->tau > 0.0))) return ZO_EINVAL;
+    const int b = s->b, d = s->d;
+    const size_t Tmax = (size_t)bt->max_blocks * b;
+    const long units = (long)bt->B * s->L * s->h_kv;
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long unit = 0; unit < units; unit++) {
+        int h = (int)(unit % s->h_kv), l = (int)((unit / s->h_kv) % s->L), n = (int)(unit / ((long)s->h_kv * s->L));
+        int N = bt->num_blocks[n], T = N * b, vl = unit_valid_len(s, bt, n, l, h), Tv = vl + b;
+        const int32_t *tbl = bt->block_table + (size_t)n * bt->max_blocks;
+        double *S = scores + (size_t)unit * Tmax;
+        /* live sequence: pos[j] = logical position of live index j */
+        int *pos = (int *)malloc((size_t)Tv * sizeof(int));
+        double *tmp = (double *)malloc((size_t)Tv * sizeof(double));
+        double *Cm = (double *)malloc((size_t)b * b * sizeof(double));
+        if (!pos || !tmp || !Cm) { failed = 1; free(pos); free(tmp); free(Cm); continue; }
+        for (int t = 0, j = 0; t < T; t++) if (live_index(t, N, b, vl) >= 0) pos[j++] = t;
+        /* global score */
+        if (ex->F) {
+            const int has_hist = ex->compressed && ex->compressed[n];
+            for (int j = 0; j < Tv; j++) {
+                int t = pos[j];
+                size_t fi = f_index(s, l, tbl[t / b], t % b, h);
+                double v = S[t];
+                if (has_hist && t < vl) {
+                    double old = ex->alpha * (double)ex->F[fi];
+                    if (old > v) v = old;
+                }
+                ex->F[fi] = (float)v;
+                S[t] = v;
+            }
+        }
+        /* max pooling along the live sequence */
+        if (ex->pool_kernel > 1) {
+            int r = ex->pool_kernel / 2;
+            for (int j = 0; j < Tv; j++) {
+                double m = -INFINITY;
+                for (int q = j - r; q <= j + r; q++) if (q >= 0 && q < Tv && S[pos[q]] > m) m = S[pos[q]];
+                tmp[j] = m;
+            }
+            for (int j = 0; j < Tv; j++) S[pos[j]] = tmp[j];
+        }
+        /* lightning redundancy */
+        if (ex->lambda != 0.0) {
+            for (int j = 0; j < Tv; j++) tmp[j] = 0.0;   /* row sums per live index */
+            for (int i = 0; i < N; i++) {
+                /* similarity matrix of block i: rows/cols = slots; stale slots stay zero */
+                for (int r = 0; r < b; r++)
+                    for (int c = 0; c < b; c++) {
+                        double v = 0.0;
+                        int tr = i * b + r, tc = i * b + c;
+                        if (r != c && live_index(tr, N, b, vl) >= 0 && live_index(tc, N, b, vl) >= 0) {
+                            size_t ro = kv_row(s, l, tbl[i], r, h), co = kv_row(s, l, tbl[i], c, h);
+                            double dot = 0.0, nr = 0.0, nc = 0.0;
+                            for (int e = 0; e < d; e++) {
+                                double x = elem(K, ro + e, s->dtype), y = elem(K, co + e, s->dtype);
+                                dot += x * y; nr += x * x; nc += y * y;
+                            }
+                            if (nr > 0.0 && nc > 0.0) v = dot / (sqrt(nr) * sqrt(nc));
+                        }
+                        Cm[r * b + c] = v;
+                    }
+                for (int c = 0; c < b; c++)             /* newest similar token is spared: last entry above p in the column */
+                    for (int r = b - 1; r >= 0; r--)
+                        if (Cm[r * b + c] > ex->p) { Cm[r * b + c] = 0.0; break; }
+                for (int r = 0; r < b; r++) {
+                    int j = live_index(i * b + r, N, b, vl);
+                    if (j < 0) continue;
+                    double acc = 0.0;
+                    for (int c = 0; c < b; c++) acc += Cm[r * b + c];
+                    tmp[j] = acc / (double)Tv;
+                }
+            }
+            double m = -INFINITY, z = 0.0;
+            for (int j = 0; j < Tv; j++) if (tmp[j] / ex->tau > m) m = tmp[j] / ex->tau;
+            for (int j = 0; j < Tv; j++) z += exp(tmp[j] / ex->tau - m);
+            for (int j = 0; j < Tv; j++) S[pos[j]] -= ex->lambda * exp(tmp[j] / ex->tau - m) / z;
+        }
+        free(pos); free(tmp); free(Cm);
+    }
+    return failed ? ZO_ENOMEM : ZO_OK;
+}
+
+/* The global-score cache moves with the kept entries (appendix "KV Cache Compression", last paragraph): the same
+   gather as zo_compact with a row of one fp32 value. */
+int zo_compact_global(const zo_shape *s, const zo_batch *bt, float *F, const int32_t *keep_idx, const int32_t *len) {
+    const int b = s->b, budget = (bt->N_max - 1) * b;
+    const long units = (long)bt->B * s->L * s->h_kv;
+    for (long unit = 0; unit < units; unit++) {
+        int h = (int)(unit % s->h_kv), l = (int)((unit / s->h_kv) % s->L), n = (int)(unit / ((long)s->h_kv * s->L));
+        int k = len[unit];
+        if (k < 0 || k > budget) return ZO_EINVAL;
+        const int32_t *tbl = bt->block_table + (size_t)n * bt->max_blocks;
+        const int32_t *dst = bt->dst_table ? bt->dst_table + (size_t)n * (bt->N_max - 1) : tbl;
+        const int32_t *idx = keep_idx + (size_t)unit * budget;
+        float *snap = (float *)malloc((size_t)(k ? k : 1) * sizeof(float));
+        if (!snap) return ZO_ENOMEM;
+        for (int r = 0; r < k; r++) snap[r] = F[f_index(s, l, tbl[idx[r] / b], idx[r] % b, h)];
+        for (int r = 0; r < k; r++) F[f_index(s, l, dst[r / b], r % b, h)] = snap[r];
+        free(snap);
+    }
+    return ZO_OK;
+}
+
 /* sort record for selection: score descending, then position ascending */
 typedef struct { float s; int32_t t; } zo_rec;
 static int rec_cmp(const void *pa, const void *pb) {

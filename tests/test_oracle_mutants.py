@@ -10,6 +10,7 @@ import subprocess
 import pytest
 
 import oracle
+from tests import test_oracle_extras as te
 from tests import test_oracle_plan as tp
 from tests import test_oracle_score as ts
 from tests import test_oracle_select_compact as tc
@@ -45,6 +46,18 @@ MUTANTS = [
     ("shared judged on live counts", "if (refcnt[p] > 1) {               /* shared at batch start", "if (cnt[p] > 1) {               /* shared at batch start"),
     ("targets released", "} else if (i >= N_max - 1 && i != res) {", "} else if (i != res) {"),
     ("decode attention without scale", "a[t] = acc / sqrt((double)d);", "a[t] = acc;"),
+    ("history used on a first compression", "const int has_hist = ex->compressed && ex->compressed[n];", "const int has_hist = 1;"),
+    ("history applied to the last block too", "if (has_hist && t < vl) {", "if (has_hist) {"),
+    ("decay forgotten", "double old = ex->alpha * (double)ex->F[fi];", "double old = (double)ex->F[fi];"),
+    ("cache stores the pooled score", "                ex->F[fi] = (float)v;\n                S[t] = v;", "                S[t] = v;"),
+    ("pool window one short", "for (int q = j - r; q <= j + r; q++)", "for (int q = j - r; q < j + r; q++)"),
+    ("first instead of last entry above p", "for (int r = b - 1; r >= 0; r--)\n                        if (Cm", "for (int r = 0; r < b; r++)\n                        if (Cm"),
+    ("diagonal kept", "if (r != c && live_index(tr", "if (live_index(tr"),
+    ("row sums not divided by the length", "tmp[j] = acc / (double)Tv;", "tmp[j] = acc;"),
+    ("temperature ignored", "z += exp(tmp[j] / ex->tau - m);", "z += exp(tmp[j] - m);"),
+    ("redundancy added instead of subtracted", "S[pos[j]] -= ex->lambda", "S[pos[j]] += ex->lambda"),
+    ("similarity across blocks", "size_t ro = kv_row(s, l, tbl[i], r, h), co = kv_row(s, l, tbl[i], c, h);", "size_t ro = kv_row(s, l, tbl[i], r, h), co = kv_row(s, l, tbl[(i + 1) % N], c, h);"),
+    ("global cache not moved", "for (int r = 0; r < k; r++) F[f_index(s, l, dst[r / b], r % b, h)] = snap[r];", ""),
 ]
 
 
@@ -73,6 +86,13 @@ def pins():
         tp.test_two_sharers_in_one_batch_release_the_prefix_together,
         lambda: tp.test_conservation_laws(0),
         tp.test_decode_attention_is_textbook_softmax_attention,
+        te.test_global_score_first_compression_only_stores,
+        te.test_global_score_decayed_max_on_the_live_prefix_only,
+        lambda: te.test_pooling_is_library_maxpool1d_along_the_live_sequence(3),
+        lambda: te.test_lightning_redundancy_matches_matrix_formulation(0, 0.2),
+        te.test_redundancy_closed_forms,
+        te.test_order_of_the_refinements,
+        te.test_global_cache_moves_with_the_kept_entries,
     ]
     return out
 
