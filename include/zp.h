@@ -149,6 +149,42 @@ zp_status zp_compact_kv(zp_ctx *ctx, const zp_pool *pool, const zp_batch *batch,
 zp_status zp_compress(zp_ctx *ctx, const zp_pool *pool, const zp_batch *batch, int32_t *len_out,
                       float *scores_dbg, int32_t *keep_idx_dbg, void *stream);
 
+/*
+ * Score refinements layered on the attention score, in the paper's order (appendix "Global Score", "Pooling at
+ * the Sequence Dimension", "Lightning Redundancy", "Combining All These Techniques"):
+ *   global score   S[t] <- max(alpha * F[t], S[t]) on the live prefix [0, valid_len) of a request that was
+ *                  compressed before (compressed[n] != 0), then F[t] <- S[t] for every live position;
+ *   max pooling    along the live sequence, odd kernel, stride 1, -inf padding;
+ *   redundancy     S <- S - lambda * R, R = softmax over the live sequence, temperature tau, of the row sums
+ *                  (divided by the live length) of the cosine similarity between the live keys of one physical
+ *                  block, diagonal zeroed and, in every column, the last (newest) entry above p zeroed.
+ * All fields by value except the two [dev] arrays.  A zeroed struct with pool_kernel = 1 changes nothing.
+ */
+typedef struct {
+    float *F;                  /* [dev] fp32 [L_slab][N_total][b][h_kv] global-score cache of the slab, updated in
+                                  place; NULL = no global score */
+    const int32_t *compressed; /* [dev] [B] nonzero: the request has history in F; NULL = no request has */
+    float alpha;               /* decay of the history */
+    int32_t pool_kernel;       /* odd >= 1; 1 = no pooling */
+    float lambda, tau, p;      /* redundancy weight (0 = off), temperature (> 0), similarity threshold */
+} zp_extras;
+
+/* zp_score followed by the refinements.  With F set, F is written at every live source position of every unit
+   (blocks shared by several requests of the batch receive the value of whichever sharer writes last). */
+zp_status zp_score_ex(zp_ctx *ctx, const zp_pool *pool, const zp_batch *batch, const zp_extras *extras, float *scores,
+                      void *stream);
+
+/* zp_compact_kv that also moves the cached global scores of the kept entries (appendix "KV Cache Compression",
+   last paragraph): F[target row r] <- F[source row keep_idx[r]].  F as in zp_extras; NULL = zp_compact_kv.  With
+   source blocks shared inside the batch use zp_compress_ex instead: this call reads the values back from F. */
+zp_status zp_compact_kv_ex(zp_ctx *ctx, const zp_pool *pool, const zp_batch *batch, float *F, const int32_t *keep_idx,
+                           const int32_t *len, void *stream);
+
+/* zp_compress with the refinements; with F set the kept entries' global scores travel to the targets inside the
+   kernel (on-chip copy, so shared source blocks are safe).  scores_dbg receives the refined scores. */
+zp_status zp_compress_ex(zp_ctx *ctx, const zp_pool *pool, const zp_batch *batch, const zp_extras *extras,
+                         int32_t *len_out, float *scores_dbg, int32_t *keep_idx_dbg, void *stream);
+
 /* Waits for the stream and reports whether any kernel launched through ctx since the
    last call skipped a unit (ZP_EINVAL, with the first offending unit in the error text). */
 zp_status zp_sync_status(zp_ctx *ctx, void *stream);

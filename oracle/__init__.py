@@ -54,7 +54,7 @@ def _load():
     global _lib
     if _lib is None:
         _lib = ctypes.CDLL(build())
-        for name in ("zo_score", "zo_select", "zo_compact", "zo_plan", "zo_decode_attention", "zo_threads", "zo_score_ex", "zo_compact_global"):
+        for name in ("zo_score", "zo_select", "zo_compact", "zo_plan", "zo_decode_attention", "zo_threads", "zo_score_ex", "zo_refine", "zo_compact_global"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -156,6 +156,21 @@ def score_ex(p: Problem, ex: Extras) -> np.ndarray:
     out = np.empty((bt.B, L, h_kv, bt.max_blocks * b), dtype=np.float64)
     _check(_load().zo_score_ex(ctypes.byref(sh), ctypes.byref(bt), ctypes.c_void_p(p.K.ctypes.data), ctypes.c_void_p(p.Q.ctypes.data),
                                ctypes.byref(cx), ctypes.c_void_p(out.ctypes.data)), "score_ex")
+    return out
+
+
+def refine(p: Problem, ex: Extras, scores: np.ndarray) -> np.ndarray:
+    """The refinements of score_ex applied to given scores (any float type; computed in fp64); ex.F is updated in place."""
+    sh, bt, keepalive = _structs(p)
+    L, _, b, h_kv = p.K.shape[:4]
+    if ex.F is not None:
+        assert ex.F.dtype == np.float32 and ex.F.flags.c_contiguous and ex.F.shape == p.K.shape[:4]
+    comp = _i32(ex.compressed)
+    cx = _Extras(_ptr(ex.F), _ptr(comp), ex.alpha, ex.pool_kernel, ex.lam, ex.tau, ex.p)
+    out = np.ascontiguousarray(scores, dtype=np.float64).copy()
+    assert out.shape == (bt.B, L, h_kv, bt.max_blocks * b)
+    _check(_load().zo_refine(ctypes.byref(sh), ctypes.byref(bt), ctypes.c_void_p(p.K.ctypes.data), ctypes.byref(cx),
+                             ctypes.c_void_p(out.ctypes.data)), "refine")
     return out
 
 

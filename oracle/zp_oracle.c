@@ -237,9 +237,9 @@ static size_t f_index(const zo_shape *s, int l, int blk, int slot, int h) {
     return (((size_t)l * s->N_total + blk) * s->b + slot) * s->h_kv + h;
 }
 
-int zo_score_ex(const zo_shape *s, const zo_batch *bt, const void *K, const void *Q, const zo_extras *ex, double *scores) {
-    int rc = zo_score(s, bt, K, Q, scores);
-    if (rc || !ex) return rc;
+/* The refinements applied to scores that are already there (scores: [units][max_blocks*b] fp64, in place). */
+int zo_refine(const zo_shape *s, const zo_batch *bt, const void *K, const zo_extras *ex, double *scores) {
+    if (!ex) return ZO_OK;
     if (ex->pool_kernel < 1 || !(ex->pool_kernel & 1) || (ex->lambda != 0.0 && !(ex->tau > 0.0))) return ZO_EINVAL;
     const int b = s->b, d = s->d;
     const size_t Tmax = (size_t)bt->max_blocks * b;
@@ -321,6 +321,11 @@ int zo_score_ex(const zo_shape *s, const zo_batch *bt, const void *K, const void
         free(pos); free(tmp); free(Cm);
     }
     return failed ? ZO_ENOMEM : ZO_OK;
+}
+
+int zo_score_ex(const zo_shape *s, const zo_batch *bt, const void *K, const void *Q, const zo_extras *ex, double *scores) {
+    int rc = zo_score(s, bt, K, Q, scores);
+    return rc ? rc : zo_refine(s, bt, K, ex, scores);
 }
 
 /* The global-score cache moves with the kept entries (appendix "KV Cache Compression", last paragraph): the same

@@ -21,7 +21,8 @@ ZP_F32, ZP_BF16 = 0, 1
 ZP_OPT_SPLIT, ZP_OPT_SPIN_LIMIT, ZP_OPT_STREAMS = 1, 2, 3
 
 EXPORTS = ("zp_create", "zp_destroy", "zp_last_error", "zp_scratch_bytes", "zp_score", "zp_select_topk", "zp_compact_kv",
-           "zp_compress", "zp_sync_status", "zp_validate_batch", "zp_plan", "zp_set_option", "zp_decode_attention")
+           "zp_compress", "zp_sync_status", "zp_validate_batch", "zp_plan", "zp_set_option", "zp_decode_attention", "zp_score_ex",
+           "zp_compact_kv_ex", "zp_compress_ex")
 
 
 class ZpError(RuntimeError):
@@ -38,6 +39,11 @@ class _Pool(ctypes.Structure):
 class _Batch(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("B", "N_max", "max_blocks", "L")] + [
         (n, ctypes.c_void_p) for n in ("block_table", "dst_table", "num_blocks", "q_slot", "valid_len", "keep")]
+
+
+class _Extras(ctypes.Structure):
+    _fields_ = [("F", ctypes.c_void_p), ("compressed", ctypes.c_void_p), ("alpha", ctypes.c_float), ("pool_kernel", ctypes.c_int32),
+                ("lam", ctypes.c_float), ("tau", ctypes.c_float), ("p", ctypes.c_float)]
 
 
 _lib = None
@@ -103,6 +109,25 @@ class Batch:
         B, max_blocks = self.block_table.shape
         return _Batch(B, self.N_max, max_blocks, self.L, _i32ptr(self.block_table), _i32ptr(self.dst_table),
                       _i32ptr(self.num_blocks), _i32ptr(self.q_slot), _i32ptr(self.valid_len), _i32ptr(self.keep))
+
+
+@dataclass
+class Extras:
+    """Score refinements (see zp_extras in include/zp.h)."""
+    F: Optional[torch.Tensor] = None            # [L_slab, N_total, b, h_kv] float32, updated in place
+    compressed: Optional[torch.Tensor] = None   # [B] int32
+    alpha: float = 0.8
+    pool_kernel: int = 1
+    lam: float = 0.0
+    tau: float = 1.0
+    p: float = 1.0
+
+    def c(self, pool: _Pool) -> _Extras:
+        if self.F is not None:
+            assert self.F.is_cuda and self.F.dtype == torch.float32 and self.F.is_contiguous()
+            assert tuple(self.F.shape) == (pool.L_slab, pool.N_total, pool.b, pool.h_kv)
+        return _Extras(None if self.F is None else self.F.data_ptr(), _i32ptr(self.compressed), self.alpha, self.pool_kernel,
+                       self.lam, self.tau, self.p)
 
 
 def _stream() -> ctypes.c_void_p:
@@ -173,6 +198,36 @@ class Context:
         self._check(self.lib.zp_compress(self.h, ctypes.byref(p), ctypes.byref(b), ctypes.c_void_p(len_out.data_ptr()),
                                          ctypes.c_void_p(scores_dbg.data_ptr() if scores_dbg is not None else None),
                                          ctypes.c_void_p(keep_idx_dbg.data_ptr() if keep_idx_dbg is not None else None), _stream()))
+
+    def zp_score_ex(self, pool: Pool, batch: Batch, extras: Extras, scores: torch.Tensor) -> None:
+        assert scores.is_cuda and scores.dtype == torch.float32 and scores.is_contiguous()
+        p, b = pool.c(), batch.c()
+        x = extras.c(p)
+        assert scores.numel() == b.B * p.L_slab * p.h_kv * b.max_blocks * p.b
+        self._check(self.lib.zp_score_ex(self.h, ctypes.byref(p), ctypes.byref(b), ctypes.byref(x), ctypes.c_void_p(scores.data_ptr()), _stream()))
+
+    def zp_compact_kv_ex(self, pool: Pool, batch: Batch, F: torch.Tensor, keep_idx: torch.Tensor, length: torch.Tensor) -> None:
+        assert keep_idx.is_cuda and keep_idx.dtype == torch.int32 and length.dtype == torch.int32
+        p, b = pool.c(), batch.c()
+        units = b.B * p.L_slab * p.h_kv
+        assert keep_idx.numel() == units * (b.N_max - 1) * p.b and length.numel() == units
+        assert F.is_cuda and F.dtype == torch.float32 and F.is_contiguous() and tuple(F.shape) == (p.L_slab, p.N_total, p.b, p.h_kv)
+        self._check(self.lib.zp_compact_kv_ex(self.h, ctypes.byref(p), ctypes.byref(b), ctypes.c_void_p(F.data_ptr()),
+                                              ctypes.c_void_p(keep_idx.data_ptr()), ctypes.c_void_p(length.data_ptr()), _stream()))
+
+    def zp_compress_ex(self, pool: Pool, batch: Batch, extras: Extras, len_out: torch.Tensor, scores_dbg: Optional[torch.Tensor] = None,
+                       keep_idx_dbg: Optional[torch.Tensor] = None) -> None:
+        p, b = pool.c(), batch.c()
+        x = extras.c(p)
+        units = b.B * p.L_slab * p.h_kv
+        assert len_out.is_cuda and len_out.dtype == torch.int32 and len_out.numel() == units
+        if scores_dbg is not None:
+            assert scores_dbg.dtype == torch.float32 and scores_dbg.is_contiguous() and scores_dbg.numel() == units * b.max_blocks * p.b
+        if keep_idx_dbg is not None:
+            assert keep_idx_dbg.dtype == torch.int32 and keep_idx_dbg.is_contiguous() and keep_idx_dbg.numel() == units * (b.N_max - 1) * p.b
+        self._check(self.lib.zp_compress_ex(self.h, ctypes.byref(p), ctypes.byref(b), ctypes.byref(x), ctypes.c_void_p(len_out.data_ptr()),
+                                            ctypes.c_void_p(scores_dbg.data_ptr() if scores_dbg is not None else None),
+                                            ctypes.c_void_p(keep_idx_dbg.data_ptr() if keep_idx_dbg is not None else None), _stream()))
 
     def zp_decode_attention(self, pool: Pool, table: torch.Tensor, length: torch.Tensor, q: torch.Tensor, out: torch.Tensor) -> None:
         """Check-only paged decode attention; q [B, L_slab, h_q, d] (pool dtype), out fp32 of the same shape."""

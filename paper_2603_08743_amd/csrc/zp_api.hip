@@ -104,7 +104,7 @@ extern "C" zp_status zp_set_option(zp_ctx *ctx, int32_t option, int32_t value) {
 
 // Scalar checks shared by every call, and the kernel argument block.  `need_q`: the call scores.
 static zp_status prepare(zp_ctx *ctx, const char *who, const zp_pool *p, const zp_batch *b, bool need_q, zp::Args *a,
-                         Path *path, int *NW, int *RB) {
+                         Path *path, int *NW, int *RB, const zp_extras *ex = nullptr, bool fused = false) {
     if (!ctx) return fail(nullptr, ZP_EINVAL, "%s: ctx is NULL", who);
     if (!p || !b) return fail(ctx, ZP_EINVAL, "%s: pool or batch is NULL", who);
     if (p->dtype != ZP_F32 && p->dtype != ZP_BF16) return fail(ctx, ZP_EINVAL, "%s: unknown dtype %d", who, p->dtype);
@@ -150,11 +150,27 @@ static zp_status prepare(zp_ctx *ctx, const char *who, const zp_pool *p, const z
         score_bytes = zp::mfma_union_bytes(a->d, *NW, *NW * *RB);
     }
     if (!need_q) score_bytes = 0;
+    // score refinements (they run in the tail of the one-workgroup-per-unit kernels only)
+    if (ex) {
+        if (ex->pool_kernel < 1 || !(ex->pool_kernel & 1)) return fail(ctx, ZP_EINVAL, "%s: pool_kernel %d must be odd and >= 1", who, ex->pool_kernel);
+        if (ex->lambda != 0.f && !(ex->tau > 0.f && std::isfinite(ex->tau))) return fail(ctx, ZP_EINVAL, "%s: tau must be positive", who);
+        if (ex->F && (long long)p->L_slab * p->N_total * p->b * p->h_kv > 0xffffffffLL)
+            return fail(ctx, ZP_EUNSUPPORTED, "%s: global-score cache of more than 2^32-1 entries per slab", who);
+        if (ex->F) a->ex |= zp::EX_GLOBAL | (fused ? zp::EX_MOVE_F_LDS : 0);
+        if (ex->pool_kernel > 1) a->ex |= zp::EX_POOL;
+        if (ex->lambda != 0.f) a->ex |= zp::EX_RED;
+        a->F = ex->F; a->compressed = ex->compressed; a->alpha = ex->alpha; a->lambda = ex->lambda; a->p_thr = ex->p;
+        a->inv_tau_log2 = ex->lambda != 0.f ? (float)(1.4426950408889634 / (double)ex->tau) : 0.f;
+        a->pool_r = ex->pool_kernel / 2;
+    }
+    const bool red_mfma = *path == PATH_MFMA && a->b_shift >= 0 && p->b <= 32;
+    const size_t refine_bytes = !a->ex ? 0 : ((a->ex & (zp::EX_POOL | zp::EX_RED)) ? (size_t)a->T_max * 4 : 0) +
+                                ((a->ex & zp::EX_RED) ? (red_mfma ? (size_t)*NW * 96 * 4 : (size_t)a->T_max * 12) : 0);
     const size_t list_bytes = (size_t)a->budget * 4;
     const int misc_bytes = align16((int)sizeof(int) * (256 + 16 + 4));
     // automatic = one workgroup per unit: measured on MI355X, the split path is bound by the latency of its
     // exchange steps (20 ms against 12.5 ms for the scoring of one 8-layer slab of the 8B-like shape)
-    if (*path == PATH_MFMA && ctx->split_mode == 1) {
+    if (*path == PATH_MFMA && ctx->split_mode == 1 && !a->ex) {
         // split path: misc first, then either (key chunk, wave partials) or (S, tables, kept list)
         const int nsub_max = (a->T_max + 31) / 32;
         a->C = (nsub_max + zp::SPLIT_SUBS - 1) / zp::SPLIT_SUBS;
@@ -184,7 +200,10 @@ static zp_status prepare(zp_ctx *ctx, const char *who, const zp_pool *p, const z
     a->off_dst = a->off_tbl + align16(a->max_blocks * 4);
     a->off_misc = a->off_dst + align16((a->N_max - 1) * 4);
     a->off_union = a->off_misc + misc_bytes;
-    const size_t total = (size_t)a->off_union + (score_bytes > list_bytes ? score_bytes : list_bytes);
+    size_t union_bytes = score_bytes > list_bytes ? score_bytes : list_bytes;
+    if (refine_bytes > union_bytes) union_bytes = refine_bytes;
+    a->off_G = a->off_union + align16((int)union_bytes);
+    const size_t total = (size_t)a->off_G + ((a->ex & zp::EX_MOVE_F_LDS) ? (size_t)a->T_max * 4 : 0);
     if (total > (size_t)kLdsLimit)
         return fail(ctx, ZP_EUNSUPPORTED, "%s: %zu bytes of LDS per unit exceed %d (max_blocks*b too large)", who, total, kLdsLimit);
     a->lds_bytes = (int)align16((int)total);
@@ -237,6 +256,18 @@ extern "C" zp_status zp_score(zp_ctx *ctx, const zp_pool *pool, const zp_batch *
     return launch(ctx, "zp_score", a, path, NW, RB, stream);
 }
 
+extern "C" zp_status zp_score_ex(zp_ctx *ctx, const zp_pool *pool, const zp_batch *batch, const zp_extras *extras, float *scores,
+                                 void *stream) {
+    if (!extras) return zp_score(ctx, pool, batch, scores, stream);
+    zp::Args a; Path path; int NW, RB;
+    zp_status rc = prepare(ctx, "zp_score_ex", pool, batch, true, &a, &path, &NW, &RB, extras, false);
+    if (rc) return rc;
+    if (!scores && batch->B > 0) return fail(ctx, ZP_EINVAL, "zp_score_ex: scores is NULL");
+    a.stages = zp::STAGE_SCORE;
+    a.scores_out = scores;
+    return launch(ctx, "zp_score_ex", a, path, NW, RB, stream);
+}
+
 extern "C" zp_status zp_select_topk(zp_ctx *ctx, const float *scores, int32_t T_max, const zp_pool *pool, const zp_batch *batch,
                                     int32_t *keep_idx, int32_t *len_out, void *stream) {
     zp::Args a; Path path; int NW, RB;
@@ -259,6 +290,33 @@ extern "C" zp_status zp_compact_kv(zp_ctx *ctx, const zp_pool *pool, const zp_ba
     a.stages = zp::STAGE_LOAD_LIST | zp::STAGE_COMPACT;
     a.keep_idx_in = keep_idx; a.len_in = len;
     return launch(ctx, "zp_compact_kv", a, PATH_GENERIC, NW, RB, stream);
+}
+
+extern "C" zp_status zp_compact_kv_ex(zp_ctx *ctx, const zp_pool *pool, const zp_batch *batch, float *F, const int32_t *keep_idx,
+                                      const int32_t *len, void *stream) {
+    if (!F) return zp_compact_kv(ctx, pool, batch, keep_idx, len, stream);
+    zp::Args a; Path path; int NW, RB;
+    zp_status rc = prepare(ctx, "zp_compact_kv_ex", pool, batch, false, &a, &path, &NW, &RB);
+    if (rc) return rc;
+    if ((!keep_idx || !len) && batch->B > 0) return fail(ctx, ZP_EINVAL, "zp_compact_kv_ex: keep_idx / len is NULL");
+    if ((long long)pool->L_slab * pool->N_total * pool->b * pool->h_kv > 0xffffffffLL)
+        return fail(ctx, ZP_EUNSUPPORTED, "zp_compact_kv_ex: global-score cache of more than 2^32-1 entries per slab");
+    a.stages = zp::STAGE_LOAD_LIST | zp::STAGE_COMPACT;
+    a.keep_idx_in = keep_idx; a.len_in = len;
+    a.F = F; a.ex = zp::EX_MOVE_F;
+    return launch(ctx, "zp_compact_kv_ex", a, PATH_GENERIC, NW, RB, stream);
+}
+
+extern "C" zp_status zp_compress_ex(zp_ctx *ctx, const zp_pool *pool, const zp_batch *batch, const zp_extras *extras, int32_t *len_out,
+                                    float *scores_dbg, int32_t *keep_idx_dbg, void *stream) {
+    if (!extras) return zp_compress(ctx, pool, batch, len_out, scores_dbg, keep_idx_dbg, stream);
+    zp::Args a; Path path; int NW, RB;
+    zp_status rc = prepare(ctx, "zp_compress_ex", pool, batch, true, &a, &path, &NW, &RB, extras, true);
+    if (rc) return rc;
+    if (!len_out && batch->B > 0) return fail(ctx, ZP_EINVAL, "zp_compress_ex: len_out is NULL");
+    a.stages = zp::STAGE_SCORE | zp::STAGE_SELECT | zp::STAGE_COMPACT;
+    a.scores_out = scores_dbg; a.keep_idx_out = keep_idx_dbg; a.len_out = len_out;
+    return launch(ctx, "zp_compress_ex", a, path, NW, RB, stream);
 }
 
 extern "C" zp_status zp_compress(zp_ctx *ctx, const zp_pool *pool, const zp_batch *batch, int32_t *len_out, float *scores_dbg,

@@ -37,6 +37,17 @@ __device__ __forceinline__ size_t row_off(const Args &a, int ls, int blk, int sl
     return ((((size_t)ls * a.N_total + blk) * a.b + slot) * a.h_kv + h) * (size_t)a.row_bytes;
 }
 
+// logical position -> live index, -1 for a stale position
+__device__ __forceinline__ int pos_to_live(const Unit &u, const Args &a, int t) {
+    const int lb = (u.N - 1) * a.b;
+    return t < u.vl ? t : (t >= lb ? t - lb + u.vl : -1);
+}
+
+// element index into the global-score cache F [L_slab][N_total][b][h_kv] (host-checked to fit 32 bits)
+__device__ __forceinline__ unsigned f_off(const Args &a, int ls, int blk, int slot, int h) {
+    return (((unsigned)ls * (unsigned)a.N_total + (unsigned)blk) * (unsigned)a.b + (unsigned)slot) * (unsigned)a.h_kv + (unsigned)h;
+}
+
 __device__ __forceinline__ void report_bad(const Args &a, int unit, int reason) {
     if (a.len_out) a.len_out[unit] = -1;
     if (atomicCAS(&a.status[0], 0, 1) == 0) {
@@ -210,15 +221,17 @@ __device__ inline void select_unit(const Args &a, const Unit &u, unsigned *keys,
 // row of a chunk is in registers (loads complete) before the barrier that precedes the chunk's
 // stores, and a later chunk only reads positions at or beyond its own ranks, so its loads may be in
 // flight while the previous chunk is being stored (two register sets, loads and stores overlap).
-template <int U> struct RowSet {
+template <int U, int FM> struct RowSet {   // FM: 0 K/V only, 1 F read back from global memory, 2 F from the on-chip copy
     u32x4 kk[U], vv[U];
     size_t dof[U];
     bool mv[U];
+    float fv[FM ? U : 1];
+    unsigned fdo[FM ? U : 1];
 };
 
-template <int U>
-__device__ __forceinline__ void rows_load(const Args &a, const Unit &u, const int *tbl, const int *dst, const int *list, int k,
-                                          int r0, int rpp, int rsub, int ch, bool active, RowSet<U> &s) {
+template <int U, int FM>
+__device__ __forceinline__ void rows_load(const Args &a, const Unit &u, const int *tbl, const int *dst, const int *list, const float *Sg, int k,
+                                          int r0, int rpp, int rsub, int ch, bool active, RowSet<U, FM> &s) {
 #pragma unroll
     for (int i = 0; i < U; i++) {
         const int r = r0 + i * rpp + rsub;
@@ -232,23 +245,29 @@ __device__ __forceinline__ void rows_load(const Args &a, const Unit &u, const in
                 s.mv[i] = true;
                 s.kk[i] = *(const u32x4 *)(a.k + so);
                 s.vv[i] = *(const u32x4 *)(a.v + so);
+                if (FM && ch == 0) {                             // one lane per row carries the cached global score
+                    s.fdo[i] = f_off(a, u.ls, dst[db], r - db * a.b, u.h);
+                    s.fv[i] = FM == 2 ? Sg[t] : a.F[f_off(a, u.ls, tbl[sb], t - sb * a.b, u.h)];
+                }
             }
         }
     }
 }
 
-template <int U>
-__device__ __forceinline__ void rows_store(const Args &a, const RowSet<U> &s) {
+template <int U, int FM>
+__device__ __forceinline__ void rows_store(const Args &a, int ch, const RowSet<U, FM> &s) {
 #pragma unroll
     for (int i = 0; i < U; i++) {
         if (s.mv[i]) {
             *(u32x4 *)(a.k + s.dof[i]) = s.kk[i];
             *(u32x4 *)(a.v + s.dof[i]) = s.vv[i];
+            if (FM && ch == 0) a.F[s.fdo[i]] = s.fv[i];
         }
     }
 }
 
-__device__ inline void compact_unit(const Args &a, const Unit &u, const int *tbl, const int *dst, const int *list, int k) {
+template <int FM>
+__device__ inline void compact_unit(const Args &a, const Unit &u, const int *tbl, const int *dst, const int *list, const float *Sg, int k) {
     const int tid = threadIdx.x;
     const int cpr = a.row_bytes >> 4;                            // 16-byte pieces per row
     const int rpp = blockDim.x / cpr;                            // rows per pass
@@ -256,23 +275,249 @@ __device__ inline void compact_unit(const Args &a, const Unit &u, const int *tbl
     const bool active = rsub < rpp;
     constexpr int U = ZP_COMPACT_U;
     const int CH = U * rpp;                                      // rows per chunk
-    RowSet<U> A, B;
-    if (k > 0) rows_load<U>(a, u, tbl, dst, list, k, 0, rpp, rsub, ch, active, A);
+    RowSet<U, FM> A, B;
+    if (k > 0) rows_load<U, FM>(a, u, tbl, dst, list, Sg, k, 0, rpp, rsub, ch, active, A);
 #pragma unroll 1
     for (int r0 = 0; r0 < k; r0 += 2 * CH) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        if (r0 + CH < k) rows_load<U>(a, u, tbl, dst, list, k, r0 + CH, rpp, rsub, ch, active, B);
-        rows_store<U>(a, A);
+        if (r0 + CH < k) rows_load<U, FM>(a, u, tbl, dst, list, Sg, k, r0 + CH, rpp, rsub, ch, active, B);
+        rows_store<U, FM>(a, ch, A);
         if (r0 + CH >= k) break;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        if (r0 + 2 * CH < k) rows_load<U>(a, u, tbl, dst, list, k, r0 + 2 * CH, rpp, rsub, ch, active, A);
-        rows_store<U>(a, B);
+        if (r0 + 2 * CH < k) rows_load<U, FM>(a, u, tbl, dst, list, Sg, k, r0 + 2 * CH, rpp, rsub, ch, active, A);
+        rows_store<U, FM>(a, ch, B);
     }
 }
 
-// Everything after S sits in LDS: optional score output, selection, optional list output, compaction.
+// ------------------------------------------------------------------ score refinements
+//
+// Applied to S (LDS, indexed by logical position) right after scoring, in the paper's order (appendix
+// "Combining All These Techniques"): global score -> max pooling -> S - lambda * R.
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+// workgroup-wide max and sum of per-thread values, same result in every thread, fixed order
+__device__ inline float block_reduce(float v, bool is_max, Misc *misc) {
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, nw = blockDim.x >> 6;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float o = __shfl_xor(v, off);
+        v = is_max ? fmaxf(v, o) : v + o;
+    }
+    float *sc = (float *)misc->scan;
+    __syncthreads();
+    if (lane == 0) sc[wv] = v;
+    __syncthreads();
+    v = sc[0];
+    for (int i = 1; i < nw; i++) v = is_max ? fmaxf(v, sc[i]) : v + sc[i];
+    return v;
+}
+
+// Lightning redundancy, any element type and block size (appendix "Lightning Redundancy"): one thread per
+// live key computes its row of the within-block cosine-similarity matrix on the vector ALUs.  The matrix is
+// symmetric, so the row of key r is also column r: the thread finds the last entry above p of its column
+// there and publishes (row, value); row sums are corrected after a barrier.  rs[j] receives the row sum / Tv.
+template <int DT>
+__device__ inline void redundancy_valu(const Args &a, const Unit &u, const int *tbl, float *rs, float *inv, int *zl, float *zv) {
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int n_el = a.d;
+    for (int j = tid; j < u.Tv; j += nt) {
+        const int t = live_to_pos(u, a, j), blk = div_b(a, t);
+        const char *kr = a.k + row_off(a, u.ls, tbl[blk], t - blk * a.b, u.h);
+        float n2 = 0.f;
+        for (int e = 0; e < n_el; e++) {
+            const float x = DT ? __uint_as_float((unsigned)((const unsigned short *)kr)[e] << 16) : ((const float *)kr)[e];
+            n2 = fmaf(x, x, n2);
+        }
+        inv[j] = n2 > 0.f ? 1.0f / sqrtf(n2) : 0.f;
+    }
+    __syncthreads();
+    for (int j = tid; j < u.Tv; j += nt) {
+        const int t = live_to_pos(u, a, j), blk = div_b(a, t), r = t - blk * a.b;
+        const char *kb = a.k + row_off(a, u.ls, tbl[blk], 0, u.h);
+        const size_t slot_bytes = (size_t)a.h_kv * a.row_bytes;
+        const char *kr = kb + r * slot_bytes;
+        const float ir = inv[j];
+        float acc = 0.f, lastv = 0.f;
+        int last = -1;
+        for (int c = 0; c < a.b; c++) {
+            const int jc = pos_to_live(u, a, blk * a.b + c);
+            float val = 0.f;
+            if (c != r && jc >= 0) {
+                const float ic = inv[jc];
+                if (ir != 0.f && ic != 0.f) {
+                    const char *kc = kb + c * slot_bytes;
+                    float dot = 0.f;
+                    for (int e = 0; e < n_el; e++) {
+                        const float x = DT ? __uint_as_float((unsigned)((const unsigned short *)kr)[e] << 16) : ((const float *)kr)[e];
+                        const float y = DT ? __uint_as_float((unsigned)((const unsigned short *)kc)[e] << 16) : ((const float *)kc)[e];
+                        dot = fmaf(x, y, dot);
+                    }
+                    val = dot * (ir * ic);
+                }
+            }
+            acc += val;
+            if (val > a.p_thr) { last = c; lastv = val; }
+        }
+        rs[j] = acc;
+        zl[j] = last;
+        zv[j] = lastv;
+    }
+    __syncthreads();
+    const float inv_len = 1.0f / (float)u.Tv;
+    for (int j = tid; j < u.Tv; j += nt) {
+        const int t = live_to_pos(u, a, j), blk = div_b(a, t), r = t - blk * a.b;
+        float corr = 0.f;
+        for (int c = 0; c < a.b; c++) {
+            const int jc = pos_to_live(u, a, blk * a.b + c);
+            if (jc >= 0 && zl[jc] == r) corr += zv[jc];
+        }
+        rs[j] = (rs[j] - corr) * inv_len;
+    }
+    __syncthreads();
+}
+
+// The same for bf16 keys with a block size that divides 32: K_g K_g^T of 32 consecutive logical positions
+// (32/b whole blocks) is one 32x32 tile of the matrix cores, both operands being the same register fragments.
+// Lane L, register i holds the entry (row 8*(i/4) + 4*(L/32) + i%4, column L%32); only entries whose row and
+// column lie in the same block are used.  A wave owns a group; its 96 words of LDS hold the inverse norms and
+// the (row, value) of the entry zeroed in every column.
+template <int D>
+__device__ inline void redundancy_mfma(const Args &a, const Unit &u, const int *tbl, float *rs, float *wave_scratch) {
+    constexpr int KK = D / 16;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, nw = blockDim.x >> 6, l32 = lane & 31, hf = lane >> 5;
+    float *inv = wave_scratch + wv * 96, *zv = inv + 64;
+    int *zr = (int *)(inv + 32);
+    const int ngroups = (u.T + 31) >> 5;
+    const int stale_hi = (u.N - 1) * a.b;
+    const float inv_len = 1.0f / (float)u.Tv;
+    const int cblk = l32 >> a.b_shift;                              // block of this lane's column inside the group
+    const int dgi = ((l32 >> 3) << 2) | (l32 & 3);              // register that holds the diagonal entry ...
+    const bool dg_mine = hf == ((l32 >> 2) & 1);                // ... in this half of the wave
+#pragma unroll 1
+    for (int g = wv; g < ngroups; g += nw) {
+        const int p0 = g * 32;
+        if (p0 >= u.vl && p0 + 32 <= stale_hi) continue;         // wholly stale group (same for the whole wave)
+        const int p = p0 + l32;
+        const int jl = p < u.T ? pos_to_live(u, a, p) : -1;
+        const int pc = jl >= 0 ? p : u.T - 1;                    // rows that are not live read a valid row and are masked
+        const int blk = div_b(a, pc);
+        const char *kp = a.k + row_off(a, u.ls, tbl[blk], pc - blk * a.b, u.h) + hf * 16;
+        bf16x8 kf[KK];
+#pragma unroll
+        for (int kk = 0; kk < KK; kk++) kf[kk] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(kp + kk * 32));
+        f32x16 acc;
+#pragma unroll
+        for (int i = 0; i < 16; i++) acc[i] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KK; kk++) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], kf[kk], acc, 0, 0, 0);
+        float dg = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; i++) dg = i == dgi ? acc[i] : dg;
+        if (dg_mine) inv[l32] = (jl >= 0 && dg > 0.f) ? 1.0f / sqrtf(dg) : 0.f;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // LDS serves a wave's accesses in order
+        const float ic = inv[l32];
+        float csum = 0.f, lastv = 0.f;
+        int last = -1;
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            const int row = 8 * (i >> 2) + 4 * hf + (i & 3);
+            const float ir = inv[row];
+            const bool in_blk = (row >> a.b_shift) == cblk;
+            float val = 0.f;
+            if (in_blk && row != l32 && ir != 0.f && ic != 0.f) val = acc[i] * (ir * ic);
+            csum += val;
+            if (in_blk && val > a.p_thr) { last = row; lastv = val; }   // rows ascend with i
+        }
+        const int o_last = __shfl_xor(last, 32);
+        const float o_lastv = __shfl_xor(lastv, 32), o_csum = __shfl_xor(csum, 32);
+        const float colsum = hf ? o_csum + csum : csum + o_csum;  // same bits in both halves
+        if (hf == 0) {
+            zr[l32] = last > o_last ? last : o_last;
+            zv[l32] = last > o_last ? lastv : o_lastv;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        // symmetric matrix: the sum of row r before zeroing is the sum of column r; take off what was zeroed in row r
+        if (hf == 0 && jl >= 0) {
+            float corr = 0.f;
+            const int c0 = cblk * a.b;
+            for (int c = c0; c < c0 + a.b; c++)
+                if (zr[c] == l32) corr += zv[c];
+            rs[jl] = (colsum - corr) * inv_len;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // the next group reuses the wave's scratch
+    }
+    __syncthreads();
+}
+
+// D > 0: called from the matrix-core kernel for head dimension D (bf16); D = 0: generic kernel, element type DT.
+template <int D, int DT>
+__device__ inline void refine_unit(const Args &a, const Unit &u, char *smem, const int *tbl, Misc *misc) {
+    const int tid = threadIdx.x, nt = blockDim.x;
+    float *S = (float *)(smem + a.off_S);
+    float *tmp = (float *)(smem + a.off_union);
+    if (a.ex & EX_GLOBAL) {
+        float *Sg = (float *)(smem + a.off_G);
+        const bool hist = a.compressed && a.compressed[u.n] != 0;
+        for (int j = tid; j < u.Tv; j += nt) {
+            const int t = live_to_pos(u, a, j), blk = div_b(a, t);
+            const unsigned fi = f_off(a, u.ls, tbl[blk], t - blk * a.b, u.h);
+            float v = S[t];
+            if (hist && t < u.vl) {                              // the last block holds new tokens: no history
+                const float old = a.alpha * a.F[fi];
+                if (old > v) v = old;
+            }
+            a.F[fi] = v;
+            S[t] = v;
+            if (a.ex & EX_MOVE_F_LDS) Sg[t] = v;
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // compaction may write the same cache entries later
+        __syncthreads();
+    }
+    if (a.ex & EX_POOL) {
+        const int r = a.pool_r;
+        for (int j = tid; j < u.Tv; j += nt) {
+            const int lo = j - r < 0 ? 0 : j - r, hi = j + r > u.Tv - 1 ? u.Tv - 1 : j + r;
+            float m = -INFINITY;
+            for (int q = lo; q <= hi; q++) {
+                const float x = S[live_to_pos(u, a, q)];
+                if (x > m) m = x;
+            }
+            tmp[j] = m;
+        }
+        __syncthreads();
+        for (int j = tid; j < u.Tv; j += nt) S[live_to_pos(u, a, j)] = tmp[j];
+        __syncthreads();
+    }
+    if (a.ex & EX_RED) {
+        const bool mf = D > 0 && 32 % a.b == 0;
+        if (mf) {
+            if constexpr (D > 0) redundancy_mfma<D>(a, u, tbl, tmp, tmp + a.T_max);
+        } else {
+            redundancy_valu<DT>(a, u, tbl, tmp, tmp + a.T_max, (int *)(tmp + 2 * (size_t)a.T_max), tmp + 3 * (size_t)a.T_max);
+        }
+        // R = softmax over the live sequence of (row sum / Tv) / tau, in base 2
+        float m = -INFINITY;
+        for (int j = tid; j < u.Tv; j += nt) m = fmaxf(m, tmp[j] * a.inv_tau_log2);
+        m = block_reduce(m, true, misc);
+        float z = 0.f;
+        for (int j = tid; j < u.Tv; j += nt) {
+            const float e = __builtin_amdgcn_exp2f(tmp[j] * a.inv_tau_log2 - m);
+            tmp[j] = e;
+            z += e;
+        }
+        z = block_reduce(z, false, misc);
+        const float f = a.lambda / z;
+        for (int j = tid; j < u.Tv; j += nt) S[live_to_pos(u, a, j)] -= f * tmp[j];
+        __syncthreads();
+    }
+}
+
+// Everything after S sits in LDS: refinements, optional score output, selection, optional list output, compaction.
+template <int D, int DT>
 __device__ inline void unit_tail(const Args &a, const Unit &u, char *smem, const int *tbl, const int *dst, Misc *misc) {
     const int tid = threadIdx.x, nt = blockDim.x;
     float *S = (float *)(smem + a.off_S);
@@ -282,6 +527,7 @@ __device__ inline void unit_tail(const Args &a, const Unit &u, char *smem, const
         for (int t = tid; t < u.T; t += nt) S[t] = src[t];
         __syncthreads();
     }
+    if ((a.stages & STAGE_SCORE) && (a.ex & (EX_GLOBAL | EX_POOL | EX_RED))) refine_unit<D, DT>(a, u, smem, tbl, misc);
     if (a.scores_out) {
         float *o = a.scores_out + (size_t)u.unit * a.T_max;
         for (int t = tid; t < a.T_max; t += nt) o[t] = t < u.T ? S[t] : 0.f;
@@ -309,7 +555,11 @@ __device__ inline void unit_tail(const Args &a, const Unit &u, char *smem, const
             return;
         }
     }
-    if (a.stages & STAGE_COMPACT) compact_unit(a, u, tbl, dst, list, u.k);
+    if (a.stages & STAGE_COMPACT) {
+        if (a.ex & EX_MOVE_F_LDS) compact_unit<2>(a, u, tbl, dst, list, (const float *)(smem + a.off_G), u.k);
+        else if (a.ex & EX_MOVE_F) compact_unit<1>(a, u, tbl, dst, list, nullptr, u.k);
+        else compact_unit<0>(a, u, tbl, dst, list, nullptr, u.k);
+    }
 }
 
 }  // namespace zp

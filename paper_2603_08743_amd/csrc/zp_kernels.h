@@ -14,6 +14,16 @@ enum : int {
     STAGE_LOAD_LIST = 16,   // the kept list comes from args.keep_idx_in / len_in
 };
 
+// Score refinements switched on for a launch (appendix "Global Score", "Pooling at the Sequence Dimension",
+// "Lightning Redundancy") and how compaction carries the global-score cache along.
+enum : int {
+    EX_GLOBAL = 1,     // decayed max with the cached history, cache updated
+    EX_POOL = 2,       // max pooling along the live sequence
+    EX_RED = 4,        // S - lambda * R
+    EX_MOVE_F = 8,     // compaction moves F rows read back from global memory (staged call)
+    EX_MOVE_F_LDS = 16 // compaction writes the kept entries' values from the on-chip copy made by EX_GLOBAL (fused call)
+};
+
 // Reasons a kernel skips a unit (reported through the context's status words).
 enum : int {
     BAD_NUM_BLOCKS = 1, BAD_VALID_LEN = 2, BAD_KEEP = 3, BAD_SLOT = 4, BAD_BLOCK_ID = 5, BAD_KEEP_IDX = 6, BAD_SYNC = 7,
@@ -38,6 +48,13 @@ struct Args {
     int *keep_idx_out;                         // [units][budget]
     int *len_out;                              // [units]
     int *status;                               // [4]: flag, first bad unit, reason, spare
+    // refinements
+    int ex;                                    // EX_* flags
+    float *F;                                  // [L_slab][N_total][b][h_kv] global-score cache
+    const int *compressed;                     // [B]
+    float alpha, lambda, inv_tau_log2, p_thr;  // inv_tau_log2 = log2(e) / tau
+    int pool_r;                                // pooling radius (kernel - 1) / 2
+    int off_G;                                 // LDS: [T_max] copy of the global scores for EX_MOVE_F_LDS
     // byte offsets into dynamic LDS
     int off_S, off_tbl, off_dst, off_misc, off_union, lds_bytes;
     // MFMA path geometry

@@ -16,9 +16,6 @@
 
 namespace zp {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-
 __device__ __forceinline__ float fexp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float flog2(float x) { return __builtin_amdgcn_logf(x); }
 
@@ -94,7 +91,7 @@ __global__ void __launch_bounds__(256) unit_generic(const Args a) {
     Unit u;
     if (!unit_setup(a, blockIdx.x, u, tbl, dst, misc)) return;
     if (a.stages & STAGE_SCORE) score_generic<DT>(a, u, smem, tbl);
-    unit_tail(a, u, smem, tbl, dst, misc);
+    unit_tail<0, DT>(a, u, smem, tbl, dst, misc);
 }
 
 // A workgroup may use the whole 160 KB of LDS; the runtime wants to be told once per kernel.
@@ -390,7 +387,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW
         reduce_tile(pt1, (rt - 1) * KT);
     }
     __syncthreads();
-    unit_tail(a, u, smem, tbl, dst, misc);
+    unit_tail<D, 1>(a, u, smem, tbl, dst, misc);
 }
 
 // (RB, NW) by the number of 32-row query blocks: small windows use fewer waves, large ones more rows per wave

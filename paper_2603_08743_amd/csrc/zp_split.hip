@@ -19,9 +19,6 @@
 
 namespace zp {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-
 // Data exchanged between the workgroups of a unit is written and read with relaxed device-scope atomic
 // accesses (they bypass the non-coherent cache levels), and a workgroup raises its arrival counter only after
 // s_waitcnt vmcnt(0) + barrier, i.e. once every one of its stores has completed.  Device-scope fences are
@@ -338,7 +335,7 @@ __global__ void __launch_bounds__(NW * 64) unit_split(const Args a) {
         for (int t = tid; t < u.T; t += NT) S[t] = (t < u.vl || t >= stale_hi) ? xload(&si[t]) : 0.f;
     }
     __syncthreads();
-    unit_tail(a, u, smem, tbl, dst, misc);
+    unit_tail<0, 1>(a, u, smem, tbl, dst, misc);
 }
 
 template <class K> static hipError_t allow_big_lds_split(K kernel) {
