@@ -56,6 +56,8 @@ def main():
     ap.add_argument("--batch", type=int, default=None, help="override the number of compressing requests (smaller pool too)")
     ap.add_argument("--cpu-sample-requests", type=int, default=6, help="requests (x one slab of layers) the oracle is timed on; 0 = skip")
     ap.add_argument("--no-check", action="store_true", help="skip comparing the sampled requests with the oracle")
+    ap.add_argument("--refine", default="", help="comma list of score refinements to switch on (global,pool,redundancy): times "
+                    "zp_compress_ex with the paper's recommended settings instead of the plain zp_compress")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the compression step shards without any exchange; "
@@ -95,9 +97,29 @@ def main():
     batch = binding.Batch(block_table=tbl, num_blocks=nb, q_slot=slot, N_max=w.N_max, L=w.L, keep=keep)
     pools = [binding.Pool(k=K, v=V, q=Q, layer0=s * Ls) for s in range(n_slabs)]
 
+    refine = [x for x in args.refine.split(",") if x]
+    assert all(x in ("global", "pool", "redundancy") for x in refine), "--refine takes global, pool, redundancy"
+    extras = o_extras_kw = None
+    if refine:
+        # recommended settings of the paper's ablations: alpha 0.8, lambda 0.2, tau 0.4, pooling at the first compression
+        # only; pooling kernel and similarity threshold are not given there (7 and 0.8 here); every other request has history
+        comp = (np.arange(w.B) % 2).astype(np.int32)
+        F = torch.zeros(Ls, w.N_total, w.b, w.h_kv, dtype=torch.float32, device=dev) if "global" in refine else None
+        o_extras_kw = dict(alpha=float(np.float32(0.8)), pool_kernel=7 if "pool" in refine else 1, pool_first_only=True,
+                           lam=float(np.float32(0.2)) if "redundancy" in refine else 0.0, tau=float(np.float32(0.4)), p=float(np.float32(0.8)))
+        extras = binding.Extras(F=F, compressed=torch.from_numpy(comp).to(dev), **o_extras_kw)
+
+    def compress(pool, lens, scores=None, idx=None):
+        if extras is None:
+            ctx.zp_compress(pool, batch, lens, scores, idx)
+        else:
+            ctx.zp_compress_ex(pool, batch, extras, lens, scores, idx)
+
     def restore():
         K.copy_(K0)
         V.copy_(V0)
+        if extras is not None and extras.F is not None:
+            extras.F.zero_()
 
     def one_step():
         """All slabs of one step; returns the summed device time of the zp_compress launches in ms."""
@@ -106,7 +128,7 @@ def main():
             restore()
             a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record()
-            ctx.zp_compress(pools[s], batch, len_out)
+            compress(pools[s], len_out)
             b_.record()
             evs.append((a, b_))
         torch.cuda.synchronize()
@@ -131,7 +153,7 @@ def main():
     keep_idx = torch.empty(units, w.budget, dtype=torch.int32, device=dev)
     scores_dbg = None
     sample = list(range(min(args.cpu_sample_requests, w.B)))
-    ctx.zp_compress(pools[0], batch, len_out, None, keep_idx)
+    compress(pools[0], len_out, None, keep_idx)
     ctx.zp_sync_status()
     bytes_launch, moved, kept, T_live = algorithmic_bytes(w, keep_idx, Ls, 0)
     entries_step = int(w.num_blocks.sum()) * w.b * w.L * w.h_kv
@@ -158,7 +180,15 @@ def main():
         prob = oracle.Problem(K=Kh, V=Vh, Q=Qh, block_table=sub_tbl, num_blocks=w.num_blocks[sample], q_slot=np.arange(len(sample), dtype=np.int32),
                               N_max=w.N_max, keep=None if w.keep is None else np.ascontiguousarray(w.keep[sample][:, :Ls]))
         t0 = time.time()
-        o_scores, o_idx, o_len = oracle.compress(prob)
+        if extras is None:
+            o_scores, o_idx, o_len = oracle.compress(prob)
+        else:
+            Fh = None if extras.F is None else np.zeros(Kh.shape[:4], dtype=np.float32)
+            o_scores = oracle.score_ex(prob, oracle.Extras(F=Fh, compressed=comp[sample], **o_extras_kw))
+            o_idx, o_len = oracle.select(prob, o_scores.astype(np.float32))
+            oracle.compact(prob, o_idx, o_len)
+            if Fh is not None:
+                oracle.compact_global(prob, Fh, o_idx, o_len)
         t_cpu = time.time() - t0
         n_entries = int(w.num_blocks[sample].sum()) * w.b * Ls * w.h_kv
         cpu = {"value": n_entries / t_cpu, "unit": "KV entries/s", "cores": oracle.threads(), "kind": "oracle",
@@ -180,11 +210,12 @@ def main():
         "vs_baseline": None, "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "L": w.L, "h_kv": w.h_kv, "h_q": w.h_q, "d": w.d, "b": w.b, "N_max": w.N_max, "w": w.w,
                    "budget": w.budget, "pool_blocks": w.N_total, "layers_per_launch": Ls, "launches_per_step": n_slabs,
-                   "keep": "per-head uniform [1024,4096]" if args.config == 2 else ("per-head" if w.keep is not None else "budget")},
+                   "keep": "per-head uniform [1024,4096]" if args.config == 2 else ("per-head" if w.keep is not None else "budget"),
+                   "refinements": refine},
         "request_tokens_per_s": req_tokens_step / (ms_per_step * 1e-3),
         "wall_ms_per_step_incl_restore": wall * 1e3 / args.steps,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC.get((args.config, w.B, Ls)), "kernel": "zp::unit_mfma (fused zp_compress)", "ms_per_launch": ms_per_launch,
+                     "traffic": None if refine else MEASURED_TRAFFIC.get((args.config, w.B, Ls)), "kernel": "zp::unit_mfma (fused %s)" % ("zp_compress" if extras is None else "zp_compress_ex"), "ms_per_launch": ms_per_launch,
                      "algorithmic_bytes_per_launch": bytes_launch, "moved_rows_per_launch": moved, "kept_rows_per_launch": kept},
         "cpu_baseline": cpu,
         "context": "paper: >2.1x end-to-end TPS over a Full-KV engine at ~95% accuracy, Qwen3-8B, AMC 23, budget 2048, one NVIDIA A100 (not comparable; no isolated number for this step is published)",

@@ -154,7 +154,8 @@ zp_status zp_compress(zp_ctx *ctx, const zp_pool *pool, const zp_batch *batch, i
  * the Sequence Dimension", "Lightning Redundancy", "Combining All These Techniques"):
  *   global score   S[t] <- max(alpha * F[t], S[t]) on the live prefix [0, valid_len) of a request that was
  *                  compressed before (compressed[n] != 0), then F[t] <- S[t] for every live position;
- *   max pooling    along the live sequence, odd kernel, stride 1, -inf padding;
+ *   max pooling    along the live sequence, odd kernel, stride 1, -inf padding (optionally only for requests
+ *                  without history);
  *   redundancy     S <- S - lambda * R, R = softmax over the live sequence, temperature tau, of the row sums
  *                  (divided by the live length) of the cosine similarity between the live keys of one physical
  *                  block, diagonal zeroed and, in every column, the last (newest) entry above p zeroed.
@@ -167,6 +168,8 @@ typedef struct {
     float alpha;               /* decay of the history */
     int32_t pool_kernel;       /* odd >= 1; 1 = no pooling */
     float lambda, tau, p;      /* redundancy weight (0 = off), temperature (> 0), similarity threshold */
+    int32_t pool_first_only;   /* nonzero: pool only requests without history, i.e. at their first compression
+                                  (the setting the paper's ablation recommends) */
 } zp_extras;
 
 /* zp_score followed by the refinements.  With F set, F is written at every live source position of every unit

@@ -130,7 +130,7 @@ def score(p: Problem) -> np.ndarray:
 
 class _Extras(ctypes.Structure):
     _fields_ = [("F", ctypes.c_void_p), ("compressed", ctypes.c_void_p), ("alpha", ctypes.c_double), ("pool_kernel", ctypes.c_int32),
-                ("lam", ctypes.c_double), ("tau", ctypes.c_double), ("p", ctypes.c_double)]
+                ("lam", ctypes.c_double), ("tau", ctypes.c_double), ("p", ctypes.c_double), ("pool_first_only", ctypes.c_int32)]
 
 
 @dataclass
@@ -143,6 +143,7 @@ class Extras:
     lam: float = 0.0
     tau: float = 1.0
     p: float = 1.0
+    pool_first_only: bool = False             # pool only the requests without history
 
 
 def score_ex(p: Problem, ex: Extras) -> np.ndarray:
@@ -152,7 +153,7 @@ def score_ex(p: Problem, ex: Extras) -> np.ndarray:
     if ex.F is not None:
         assert ex.F.dtype == np.float32 and ex.F.flags.c_contiguous and ex.F.shape == p.K.shape[:4]
     comp = _i32(ex.compressed)
-    cx = _Extras(_ptr(ex.F), _ptr(comp), ex.alpha, ex.pool_kernel, ex.lam, ex.tau, ex.p)
+    cx = _Extras(_ptr(ex.F), _ptr(comp), ex.alpha, ex.pool_kernel, ex.lam, ex.tau, ex.p, int(ex.pool_first_only))
     out = np.empty((bt.B, L, h_kv, bt.max_blocks * b), dtype=np.float64)
     _check(_load().zo_score_ex(ctypes.byref(sh), ctypes.byref(bt), ctypes.c_void_p(p.K.ctypes.data), ctypes.c_void_p(p.Q.ctypes.data),
                                ctypes.byref(cx), ctypes.c_void_p(out.ctypes.data)), "score_ex")
@@ -166,7 +167,7 @@ def refine(p: Problem, ex: Extras, scores: np.ndarray) -> np.ndarray:
     if ex.F is not None:
         assert ex.F.dtype == np.float32 and ex.F.flags.c_contiguous and ex.F.shape == p.K.shape[:4]
     comp = _i32(ex.compressed)
-    cx = _Extras(_ptr(ex.F), _ptr(comp), ex.alpha, ex.pool_kernel, ex.lam, ex.tau, ex.p)
+    cx = _Extras(_ptr(ex.F), _ptr(comp), ex.alpha, ex.pool_kernel, ex.lam, ex.tau, ex.p, int(ex.pool_first_only))
     out = np.ascontiguousarray(scores, dtype=np.float64).copy()
     assert out.shape == (bt.B, L, h_kv, bt.max_blocks * b)
     _check(_load().zo_refine(ctypes.byref(sh), ctypes.byref(bt), ctypes.c_void_p(p.K.ctypes.data), ctypes.byref(cx),

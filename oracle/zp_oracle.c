@@ -219,7 +219,9 @@ int zo_score(const zo_shape *s, const zo_batch *bt, const void *K, const void *Q
  *  X2 The cache F holds fp32 values; the value stored is the score after the global update, before pooling and
  *     redundancy (the paper pools "after computing the global score" and applies redundancy "after max pooling").
  *  X3 MaxPool1D: odd kernel m, stride 1, implicit -inf padding (the library default the paper uses), taken along
- *     the live sequence; the paper does not give m, so it is a parameter (1 = off).
+ *     the live sequence; the paper does not give m, so it is a parameter (1 = off).  The ablation compares pooling at
+ *     every compression with pooling at the first one only and recommends the latter: pool_first_only restricts
+ *     pooling to the requests of the batch that have no history.
  *  X4 Lightning redundancy: cosine similarity between the live keys of one physical block; diagonal zeroed; in every
  *     column the LAST (highest row, i.e. newest token) entry above the threshold p is zeroed; row sums are divided
  *     by the live sequence length Tv, then a softmax with temperature tau over the live sequence gives R.
@@ -231,6 +233,7 @@ typedef struct {
     double alpha;              /* decay of the history */
     int32_t pool_kernel;       /* odd >= 1; 1 = no pooling */
     double lambda, tau, p;     /* redundancy weight (0 = off), softmax temperature, similarity threshold */
+    int32_t pool_first_only;   /* nonzero: pool only requests without history (the setting the paper recommends) */
 } zo_extras;
 
 static size_t f_index(const zo_shape *s, int l, int blk, int slot, int h) {
@@ -258,8 +261,8 @@ int zo_refine(const zo_shape *s, const zo_batch *bt, const void *K, const zo_ext
         if (!pos || !tmp || !Cm) { failed = 1; free(pos); free(tmp); free(Cm); continue; }
         for (int t = 0, j = 0; t < T; t++) if (live_index(t, N, b, vl) >= 0) pos[j++] = t;
         /* global score */
+        const int has_hist = ex->compressed && ex->compressed[n];
         if (ex->F) {
-            const int has_hist = ex->compressed && ex->compressed[n];
             for (int j = 0; j < Tv; j++) {
                 int t = pos[j];
                 size_t fi = f_index(s, l, tbl[t / b], t % b, h);
@@ -273,7 +276,7 @@ int zo_refine(const zo_shape *s, const zo_batch *bt, const void *K, const zo_ext
             }
         }
         /* max pooling along the live sequence */
-        if (ex->pool_kernel > 1) {
+        if (ex->pool_kernel > 1 && !(ex->pool_first_only && has_hist)) {
             int r = ex->pool_kernel / 2;
             for (int j = 0; j < Tv; j++) {
                 double m = -INFINITY;

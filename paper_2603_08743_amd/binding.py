@@ -43,7 +43,7 @@ class _Batch(ctypes.Structure):
 
 class _Extras(ctypes.Structure):
     _fields_ = [("F", ctypes.c_void_p), ("compressed", ctypes.c_void_p), ("alpha", ctypes.c_float), ("pool_kernel", ctypes.c_int32),
-                ("lam", ctypes.c_float), ("tau", ctypes.c_float), ("p", ctypes.c_float)]
+                ("lam", ctypes.c_float), ("tau", ctypes.c_float), ("p", ctypes.c_float), ("pool_first_only", ctypes.c_int32)]
 
 
 _lib = None
@@ -121,13 +121,14 @@ class Extras:
     lam: float = 0.0
     tau: float = 1.0
     p: float = 1.0
+    pool_first_only: bool = False
 
     def c(self, pool: _Pool) -> _Extras:
         if self.F is not None:
             assert self.F.is_cuda and self.F.dtype == torch.float32 and self.F.is_contiguous()
             assert tuple(self.F.shape) == (pool.L_slab, pool.N_total, pool.b, pool.h_kv)
         return _Extras(None if self.F is None else self.F.data_ptr(), _i32ptr(self.compressed), self.alpha, self.pool_kernel,
-                       self.lam, self.tau, self.p)
+                       self.lam, self.tau, self.p, int(self.pool_first_only))
 
 
 def _stream() -> ctypes.c_void_p:

@@ -157,7 +157,7 @@ static zp_status prepare(zp_ctx *ctx, const char *who, const zp_pool *p, const z
         if (ex->F && (long long)p->L_slab * p->N_total * p->b * p->h_kv > 0xffffffffLL)
             return fail(ctx, ZP_EUNSUPPORTED, "%s: global-score cache of more than 2^32-1 entries per slab", who);
         if (ex->F) a->ex |= zp::EX_GLOBAL | (fused ? zp::EX_MOVE_F_LDS : 0);
-        if (ex->pool_kernel > 1) a->ex |= zp::EX_POOL;
+        if (ex->pool_kernel > 1) a->ex |= zp::EX_POOL | (ex->pool_first_only ? zp::EX_POOL_FIRST : 0);
         if (ex->lambda != 0.f) a->ex |= zp::EX_RED;
         a->F = ex->F; a->compressed = ex->compressed; a->alpha = ex->alpha; a->lambda = ex->lambda; a->p_thr = ex->p;
         a->inv_tau_log2 = ex->lambda != 0.f ? (float)(1.4426950408889634 / (double)ex->tau) : 0.f;

@@ -397,18 +397,31 @@ __device__ inline void redundancy_mfma(const Args &a, const Unit &u, const int *
     const int cblk = l32 >> a.b_shift;                              // block of this lane's column inside the group
     const int dgi = ((l32 >> 3) << 2) | (l32 & 3);              // register that holds the diagonal entry ...
     const bool dg_mine = hf == ((l32 >> 2) & 1);                // ... in this half of the wave
-#pragma unroll 1
-    for (int g = wv; g < ngroups; g += nw) {
-        const int p0 = g * 32;
-        if (p0 >= u.vl && p0 + 32 <= stale_hi) continue;         // wholly stale group (same for the whole wave)
-        const int p = p0 + l32;
-        const int jl = p < u.T ? pos_to_live(u, a, p) : -1;
-        const int pc = jl >= 0 ? p : u.T - 1;                    // rows that are not live read a valid row and are masked
+    // groups of this wave in ascending order, wholly stale ones skipped; the fragments of the next group are
+    // requested before the current one is worked on
+    auto next_group = [&](int g) {
+        while (g < ngroups && g * 32 >= u.vl && g * 32 + 32 <= stale_hi) g += nw;
+        return g;
+    };
+    auto live_of = [&](int g) {
+        const int p = g * 32 + l32;
+        return p < u.T ? pos_to_live(u, a, p) : -1;
+    };
+    auto load_group = [&](int g, bf16x8 (&kf)[KK]) {
+        const int pc = live_of(g) >= 0 ? g * 32 + l32 : u.T - 1;  // rows that are not live read a valid row and are masked
         const int blk = div_b(a, pc);
         const char *kp = a.k + row_off(a, u.ls, tbl[blk], pc - blk * a.b, u.h) + hf * 16;
-        bf16x8 kf[KK];
 #pragma unroll
         for (int kk = 0; kk < KK; kk++) kf[kk] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(kp + kk * 32));
+    };
+    bf16x8 kf[KK], kn[KK];
+    int g = next_group(wv);
+    if (g < ngroups) load_group(g, kf);
+#pragma unroll 1
+    while (g < ngroups) {
+        const int gn = next_group(g + nw);
+        if (gn < ngroups) load_group(gn, kn);
+        const int jl = live_of(g);
         f32x16 acc;
 #pragma unroll
         for (int i = 0; i < 16; i++) acc[i] = 0.f;
@@ -449,6 +462,9 @@ __device__ inline void redundancy_mfma(const Args &a, const Unit &u, const int *
             rs[jl] = (colsum - corr) * inv_len;
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // the next group reuses the wave's scratch
+#pragma unroll
+        for (int kk = 0; kk < KK; kk++) kf[kk] = kn[kk];
+        g = gn;
     }
     __syncthreads();
 }
@@ -459,9 +475,9 @@ __device__ inline void refine_unit(const Args &a, const Unit &u, char *smem, con
     const int tid = threadIdx.x, nt = blockDim.x;
     float *S = (float *)(smem + a.off_S);
     float *tmp = (float *)(smem + a.off_union);
+    const bool hist = a.compressed && a.compressed[u.n] != 0;
     if (a.ex & EX_GLOBAL) {
         float *Sg = (float *)(smem + a.off_G);
-        const bool hist = a.compressed && a.compressed[u.n] != 0;
         for (int j = tid; j < u.Tv; j += nt) {
             const int t = live_to_pos(u, a, j), blk = div_b(a, t);
             const unsigned fi = f_off(a, u.ls, tbl[blk], t - blk * a.b, u.h);
@@ -477,7 +493,7 @@ __device__ inline void refine_unit(const Args &a, const Unit &u, char *smem, con
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // compaction may write the same cache entries later
         __syncthreads();
     }
-    if (a.ex & EX_POOL) {
+    if ((a.ex & EX_POOL) && !((a.ex & EX_POOL_FIRST) && hist)) {
         const int r = a.pool_r;
         for (int j = tid; j < u.Tv; j += nt) {
             const int lo = j - r < 0 ? 0 : j - r, hi = j + r > u.Tv - 1 ? u.Tv - 1 : j + r;

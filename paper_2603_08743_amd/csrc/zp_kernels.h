@@ -21,6 +21,7 @@ enum : int {
     EX_POOL = 2,       // max pooling along the live sequence
     EX_RED = 4,        // S - lambda * R
     EX_MOVE_F = 8,     // compaction moves F rows read back from global memory (staged call)
+    EX_POOL_FIRST = 32,  // pooling only for requests without history
     EX_MOVE_F_LDS = 16 // compaction writes the kept entries' values from the on-chip copy made by EX_GLOBAL (fused call)
 };
 

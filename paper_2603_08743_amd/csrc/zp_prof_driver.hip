@@ -1,6 +1,8 @@
 // Stand-alone driver for hardware-counter runs of the fused compression kernel (no Python, no torch):
-//   rocprofv3 --pmc FETCH_SIZE -- ./zp_prof_driver [B] [L_slab] [config] [reps] [stages] [split] [streams]
+//   rocprofv3 --pmc FETCH_SIZE -- ./zp_prof_driver [B] [L_slab] [config] [reps] [stages] [split] [streams] [extras]
 // stages = 1 also times the staged calls (zp_score, zp_select_topk, zp_compact_kv) one by one.
+// extras: bit mask of score refinements to time with zp_compress_ex after the plain run (1 global score, 2 max
+// pooling with kernel 7, 4 lightning redundancy); every set of bits from 1 up to the mask that is a subset of it is run.
 // It builds one layer slab of a benchmark-shaped workload with an on-device integer-hash fill
 // (approximately N(0,1) values, 5 % of the key positions scaled x3, shuffled block tables, per-head
 // keep counts for config 2), runs a plain copy kernel of known size first (the calibration dispatch
@@ -59,6 +61,7 @@ int main(int argc, char **argv) {
     const int staged = argc > 5 ? atoi(argv[5]) : 0;
     const int split = argc > 6 ? atoi(argv[6]) : -1;
     const int streams = argc > 7 ? atoi(argv[7]) : 8;
+    const int extras = argc > 8 ? atoi(argv[8]) : 0;
     int h_kv = 8, h_q = 32, d = 128, b = 16, N_max = 257, w = 64;
     bool per_head_keep = true;
     if (cfg == 1) { h_kv = 4; h_q = 28; N_max = 129; w = 32; per_head_keep = false; }
@@ -145,6 +148,35 @@ int main(int argc, char **argv) {
             }
         }
         printf("staged: zp_score %.3f ms, zp_select_topk %.3f ms, zp_compact_kv %.3f ms per launch\n", t[0] / reps, t[1] / reps, t[2] / reps);
+    }
+    if (extras) {
+        float *F;
+        int *comp;
+        const size_t f_elems = (size_t)Ls * N_total * b * h_kv;
+        CK(hipMalloc((void **)&F, f_elems * 4));
+        CK(hipMalloc((void **)&comp, B * 4));
+        CK(hipMemset(F, 0, f_elems * 4));
+        std::vector<int> hc(B);
+        for (int n = 0; n < B; n++) hc[n] = n & 1;                 // every other request has history
+        CK(hipMemcpy(comp, hc.data(), B * 4, hipMemcpyHostToDevice));
+        for (int m = 1; m <= extras; m++) {
+            if ((m & extras) != m) continue;
+            zp_extras ex = {(m & 1) ? F : nullptr, comp, 0.8f, (m & 2) ? 7 : 1, (m & 4) ? 0.3f : 0.f, 2e-4f, 0.4f, 0};
+            double ms_sum = 0;
+            for (int r = 0; r < reps; r++) {
+                hipLaunchKernelGGL(plain_copy, dim3(16384), dim3(256), 0, 0, (const uint4 *)K0, (uint4 *)K, n16);
+                hipLaunchKernelGGL(plain_copy, dim3(16384), dim3(256), 0, 0, (const uint4 *)V0, (uint4 *)V, n16);
+                CK(hipEventRecord(e0, 0));
+                if (zp_compress_ex(ctx, &pool, &batch, &ex, d_len, nullptr, nullptr, nullptr) != ZP_OK) { fprintf(stderr, "%s\n", zp_last_error(ctx)); return 1; }
+                CK(hipEventRecord(e1, 0));
+                CK(hipEventSynchronize(e1));
+                float ms;
+                CK(hipEventElapsedTime(&ms, e0, e1));
+                ms_sum += ms;
+            }
+            if (zp_sync_status(ctx, nullptr) != ZP_OK) { fprintf(stderr, "%s\n", zp_last_error(ctx)); return 1; }
+            printf("zp_compress_ex%s%s%s: %.3f ms/launch\n", (m & 1) ? " +global" : "", (m & 2) ? " +pool7" : "", (m & 4) ? " +redundancy" : "", ms_sum / reps);
+        }
     }
     long long kept = 0;
     for (int x : keep) kept += x;

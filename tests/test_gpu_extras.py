@@ -72,6 +72,7 @@ def run_extras_protocol(p, ex_kw, history=True, seed=0, check_fused=True):
     tau = float(np.float32(ex_kw.get("tau", 1.0)))
     thr = float(np.float32(ex_kw.get("p", 1.0)))
     m = ex_kw.get("pool_kernel", 1)
+    first_only = ex_kw.get("pool_first_only", False)
     if lam != 0.0:
         assert threshold_margin(p, thr) > 1e-5, "E3: a similarity lies too close to the threshold"
     S_att = oracle.score(p)
@@ -81,12 +82,14 @@ def run_extras_protocol(p, ex_kw, history=True, seed=0, check_fused=True):
         comp = (rng.random(B) < 0.6).astype(np.int32) if history else np.zeros(B, dtype=np.int32)
         if history:
             comp[0] = 1
+            if B > 1:
+                comp[-1] = 0                                      # a mix of first and repeated compressions
 
     def o_extras(F):
-        return oracle.Extras(F=F, compressed=comp, alpha=alpha, pool_kernel=m, lam=lam, tau=tau, p=thr)
+        return oracle.Extras(F=F, compressed=comp, alpha=alpha, pool_kernel=m, lam=lam, tau=tau, p=thr, pool_first_only=first_only)
 
     def d_extras(F):
-        return binding.Extras(F=F, compressed=G.dev_i32(comp), alpha=alpha, pool_kernel=m, lam=lam, tau=tau, p=thr)
+        return binding.Extras(F=F, compressed=G.dev_i32(comp), alpha=alpha, pool_kernel=m, lam=lam, tau=tau, p=thr, pool_first_only=first_only)
 
     def fresh_F():
         return None if F0 is None else torch.from_numpy(F0).cuda()
@@ -176,6 +179,7 @@ def run_extras_protocol(p, ex_kw, history=True, seed=0, check_fused=True):
     (4, dict(B=2, L=1, h_kv=2, G=2, d=12, b=6, N_max=4, w=4, extra_blocks=2), dict(alpha=0.8, pool_kernel=7, lam=0.5, tau=0.05, p=0.35)),
     (5, dict(B=1, L=1, h_kv=2, G=1, d=24, b=8, N_max=4, w=5, bf16=True), dict(alpha=0.5, pool_kernel=3, lam=0.2, tau=0.1, p=0.3)),
     (6, dict(B=1, L=1, h_kv=1, G=2, d=8, b=4, N_max=4, w=2), dict(use_F=False, lam=0.2, tau=0.3, p=-0.5)),     # p < 0: zero entries count
+    (7, dict(B=4, L=1, h_kv=2, G=2, d=16, b=4, N_max=4, w=3, extra_blocks=1), dict(alpha=0.75, pool_kernel=3, pool_first_only=True)),
 ], ids=lambda v: str(v) if isinstance(v, int) else "")
 def test_refinements_small_problems(seed, kw, ex):
     p = random_problem(700 + seed, heavy=3, **kw)
@@ -212,7 +216,8 @@ def test_refinements_with_stale_gaps_fp32():
     (4, 16, 128, 64, 3, 1, True),       # block size off the matrix-core menu: vector-ALU redundancy inside the MFMA kernel
     (5, 32, 64, 4, 30, 3, True),
 ])
-def test_refinements_bf16(Gq, w, d, b, N_max, extra, gaps):
+@pytest.mark.parametrize("first_only", [False, True], ids=["pool-always", "pool-first"])
+def test_refinements_bf16(Gq, w, d, b, N_max, extra, gaps, first_only):
     p = random_problem(800 + Gq * 7 + w + b, B=2, L=2, h_kv=2, G=Gq, d=d, b=b, N_max=N_max, w=w, extra_blocks=extra, bf16=True, heavy=4)
     rng = np.random.default_rng(w + b)
     N = N_max + extra
@@ -227,7 +232,7 @@ def test_refinements_bf16(Gq, w, d, b, N_max, extra, gaps):
         p.keep = rng.integers(w, budget + 1, size=(2, 2, 2)).astype(np.int32)
     plant_similar_keys(p, rng, 40, noise=0.1)
     thr = pick_threshold(p, [0.4, 0.41, 0.42, 0.43])
-    rep = run_extras_protocol(p, dict(alpha=0.8, pool_kernel=5, lam=0.3, tau=0.02, p=thr), seed=b)
+    rep = run_extras_protocol(p, dict(alpha=0.8, pool_kernel=5, lam=0.3, tau=0.02, p=thr, pool_first_only=first_only), seed=b)
     assert rep["worst"] < 1e-3
 
 

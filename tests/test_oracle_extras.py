@@ -82,6 +82,19 @@ def test_pooling_is_library_maxpool1d_along_the_live_sequence(m):
         oracle.score_ex(p, oracle.Extras(pool_kernel=4))
 
 
+def test_pooling_at_the_first_compression_only():
+    b, N = 4, 5
+    p = random_problem(4, B=2, L=1, h_kv=1, G=2, d=8, b=b, N_max=4, w=2, extra_blocks=1)
+    S0 = oracle.score(p)
+    comp = np.array([1, 0], dtype=np.int32)
+    S1 = oracle.score_ex(p, oracle.Extras(compressed=comp, pool_kernel=3, pool_first_only=True))
+    want = torch.nn.functional.max_pool1d(torch.from_numpy(S0[1, 0, 0, : N * b])[None, None], 3, stride=1, padding=1)[0, 0].numpy()
+    assert np.array_equal(S1[0], S0[0])                          # has history: left alone
+    assert np.array_equal(S1[1, 0, 0, : N * b], want) and not np.array_equal(S1[1], S0[1])
+    S2 = oracle.score_ex(p, oracle.Extras(compressed=comp, pool_kernel=3))
+    assert np.array_equal(S2[1], S1[1]) and not np.array_equal(S2[0], S0[0])   # without the switch every request is pooled
+
+
 def matrix_redundancy(keys, b, live_mask, p_thr, tau):
     """Independent formulation: full cosine matrix, same-block mask, 'last above p per column' rule, row sums / Tv, softmax."""
     T = keys.shape[0]

@@ -51,6 +51,8 @@ MUTANTS = [
     ("decay forgotten", "double old = ex->alpha * (double)ex->F[fi];", "double old = (double)ex->F[fi];"),
     ("cache stores the pooled score", "                ex->F[fi] = (float)v;\n                S[t] = v;", "                S[t] = v;"),
     ("pool window one short", "for (int q = j - r; q <= j + r; q++)", "for (int q = j - r; q < j + r; q++)"),
+    ("first-only switch ignored", "if (ex->pool_kernel > 1 && !(ex->pool_first_only && has_hist)) {", "if (ex->pool_kernel > 1) {"),
+    ("first-only switch inverted", "if (ex->pool_kernel > 1 && !(ex->pool_first_only && has_hist)) {", "if (ex->pool_kernel > 1 && !(ex->pool_first_only && !has_hist)) {"),
     ("first instead of last entry above p", "for (int r = b - 1; r >= 0; r--)\n                        if (Cm", "for (int r = 0; r < b; r++)\n                        if (Cm"),
     ("diagonal kept", "if (r != c && live_index(tr", "if (live_index(tr"),
     ("row sums not divided by the length", "tmp[j] = acc / (double)Tv;", "tmp[j] = acc;"),
@@ -89,6 +91,7 @@ def pins():
         te.test_global_score_first_compression_only_stores,
         te.test_global_score_decayed_max_on_the_live_prefix_only,
         lambda: te.test_pooling_is_library_maxpool1d_along_the_live_sequence(3),
+        te.test_pooling_at_the_first_compression_only,
         lambda: te.test_lightning_redundancy_matches_matrix_formulation(0, 0.2),
         te.test_redundancy_closed_forms,
         te.test_order_of_the_refinements,
