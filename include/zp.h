@@ -103,10 +103,11 @@ const char *zp_last_error(const zp_ctx *ctx); /* ctx may be NULL: text of the la
    on one context must therefore not overlap on different streams. */
 size_t zp_scratch_bytes(const zp_pool *pool, const zp_batch *batch);
 
-/* Tuning / test switches.  ZP_OPT_SPLIT: -1 automatic (default; currently the same as 0), 0 one workgroup per
-   unit (keys swept twice from HBM), 1 several workgroups per unit with LDS-resident key chunks whenever the
-   shape allows (keys read from HBM once; needs the scratch zp_scratch_bytes reports).
-   ZP_OPT_SPIN_LIMIT: bound on the wait loop of the split path (iterations, > 0).
+/* Tuning / test switches.  ZP_OPT_SPLIT: -1 automatic (default) and 0 = one workgroup per unit (keys swept twice
+   from HBM).  1 = several workgroups per unit with LDS-resident key chunks (keys read from HBM once; needs the scratch
+   zp_scratch_bytes reports) is SWITCHED OFF in this build and returns ZP_EUNSUPPORTED: the bounded wait between the
+   workgroups of a unit has expired intermittently on MI355X and the cause is not established.
+   ZP_OPT_SPIN_LIMIT: bound on that wait loop (iterations, > 0).
    ZP_OPT_STREAMS: cap (1..8) on the ticket streams the split path orders its workgroups by. */
 typedef enum { ZP_OPT_SPLIT = 1, ZP_OPT_SPIN_LIMIT = 2, ZP_OPT_STREAMS = 3 } zp_option;
 zp_status zp_set_option(zp_ctx *ctx, int32_t option, int32_t value);

@@ -10,7 +10,17 @@
 
 namespace zp {
 
+// A workgroup may use the whole 160 KB of LDS; the runtime wants to be told once per kernel.
+template <class K> static hipError_t allow_big_lds(K kernel) {
+    static hipError_t state = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    return state;
+}
+
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+__device__ __forceinline__ float fexp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float flog2(float x) { return __builtin_amdgcn_logf(x); }
+
 
 struct Misc {            // small LDS block at Args::off_misc
     int hist[256];

@@ -48,7 +48,7 @@ struct Args {
     const int *keep_idx_in; const int *len_in;
     int *keep_idx_out;                         // [units][budget]
     int *len_out;                              // [units]
-    int *status;                               // [4]: flag, first bad unit, reason, spare
+    int *status;                               // [8]: flag, first bad unit, reason, drain flag of the split path, 4 words of detail
     // refinements
     int ex;                                    // EX_* flags
     float *F;                                  // [L_slab][N_total][b][h_kv] global-score cache
@@ -85,10 +85,18 @@ hipError_t launch_unit_generic(const Args &a, int units, hipStream_t s);
 // returns hipErrorInvalidConfiguration when no MFMA instantiation covers (d, G, w)
 bool mfma_path_available(const Args &a, int *NW, int *RB);
 hipError_t launch_unit_mfma(const Args &a, int units, int NW, int RB, hipStream_t s);
+// instantiations by head dimension and workgroup width, one translation unit each (zp_mfma_*.hip)
+hipError_t launch_mfma_d64(const Args &a, int units, int NW, int RB, hipStream_t s);
+hipError_t launch_mfma_d64_wide(const Args &a, int units, int NW, int RB, hipStream_t s);
+hipError_t launch_mfma_d128(const Args &a, int units, int NW, int RB, hipStream_t s);
+hipError_t launch_mfma_d128_wide(const Args &a, int units, int NW, int RB, hipStream_t s);
+constexpr int KT = 64;                          // keys per LDS tile of the matrix-core kernel
 size_t mfma_union_bytes(int d, int NW, int NB);
 // split path (zp_split.hip)
 constexpr int SPLIT_SUBS = 8;                  // 32-key subtiles a workgroup keeps in LDS
 hipError_t launch_unit_split(const Args &a, int units, int NW, int RB, hipStream_t s);
 hipError_t launch_zero_words(int *p, int n, hipStream_t s);
+hipError_t launch_split_d64(const Args &a, int units, int NW, int RB, hipStream_t s);
+hipError_t launch_split_d128(const Args &a, int units, int NW, int RB, hipStream_t s);
 
 }  // namespace zp

@@ -11,12 +11,22 @@ from tests.util import random_problem
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(autouse=True, params=[1, 0], ids=["split", "single"])
+SPLIT_OFF = ("the split path (several workgroups per unit) is switched off in the library: its bounded wait expired "
+             "intermittently on MI355X (reported cleanly, nothing faulted) and the cause is not established")
+
+
+@pytest.fixture(autouse=True, params=[pytest.param(1, marks=pytest.mark.skip(reason=SPLIT_OFF)), 0], ids=["split", "single"])
 def split_mode(request):
-    """Every case runs on both bf16 kernels: several workgroups per unit and one per unit."""
+    """Every case is written to run on both bf16 kernels: several workgroups per unit and one per unit."""
     G.ctx().zp_set_option(binding.ZP_OPT_SPLIT, request.param)
     yield request.param
     G.ctx().zp_set_option(binding.ZP_OPT_SPLIT, -1)
+
+
+def test_split_option_is_refused():
+    with pytest.raises(binding.ZpError) as e:
+        G.ctx().zp_set_option(binding.ZP_OPT_SPLIT, 1)
+    assert e.value.status == binding.ZP_EUNSUPPORTED
 
 
 def test_config0_tiny_fp32_exact():
