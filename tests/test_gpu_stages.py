@@ -243,3 +243,52 @@ def test_decode_attention_over_the_compacted_cache(cfg, kw):
     scale = np.abs(want).max(axis=-1, keepdims=True)
     assert np.all(np.abs(got - want) <= 1e-2 * np.abs(want) + 1e-3 * scale)
     assert np.abs(got - want).max() / np.abs(want).max() < 1e-4      # in fact far tighter than the 1e-2 the shape asks for
+
+
+def test_compression_beside_decode_on_two_streams():
+    """Asynchronous compression (Method, "Asynchronous Decoding and Compression"): some requests of a pool are compressed
+    on one stream while others decode on a second stream.  Both results must be what the calls give one after the other."""
+    w = workloads.config(2, B=4, L=1, N_total=1100)
+    p, pool, batch_all = G.workload_problem(w)
+    comp, dec = [0, 2], [1, 3]                                       # requests being compressed / decoding
+
+    def sub_batch(rows):
+        r = torch.tensor(rows, device="cuda")
+        return binding.Batch(block_table=batch_all.block_table[r].contiguous(), num_blocks=batch_all.num_blocks[r].contiguous(),
+                             q_slot=batch_all.q_slot[r].contiguous(), N_max=w.N_max, L=batch_all.L,
+                             keep=None if batch_all.keep is None else batch_all.keep[r].contiguous())
+
+    b_comp = sub_batch(comp)
+    dtab = batch_all.block_table[torch.tensor(dec, device="cuda")][:, : w.N_max].contiguous()
+    dlen = torch.full((2, 1, w.h_kv), w.N_max * w.b, dtype=torch.int32, device="cuda")
+    q = w.decode_queries("cuda")[torch.tensor(dec, device="cuda")].contiguous()
+    c = G.ctx()
+
+    def run(concurrent):
+        pl = G.clone_pool(pool)
+        s, idx, ln = G.alloc_outputs(pl, b_comp)
+        out = torch.full(q.shape, float("nan"), dtype=torch.float32, device="cuda")
+        torch.cuda.synchronize()
+        if concurrent:
+            s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+            with torch.cuda.stream(s1):
+                c.zp_compress(pl, b_comp, ln, s, idx)
+            with torch.cuda.stream(s2):
+                c.zp_decode_attention(pl, dtab, dlen, q, out)
+        else:
+            c.zp_compress(pl, b_comp, ln, s, idx)
+            c.zp_decode_attention(pl, dtab, dlen, q, out)
+        torch.cuda.synchronize()
+        c.zp_sync_status()
+        return pl, s, idx, ln, out
+
+    serial, both = run(False), run(True)
+    bits = lambda t: t.view(torch.int16) if t.dtype == torch.bfloat16 else t
+    assert torch.equal(bits(serial[0].k), bits(both[0].k)) and torch.equal(bits(serial[0].v), bits(both[0].v))
+    for a, b in zip(serial[1:], both[1:]):
+        assert torch.equal(a.view(torch.int32) if a.dtype == torch.float32 else a, b.view(torch.int32) if b.dtype == torch.float32 else b)
+    # and the compressed requests agree with the oracle's selection on the same score bits
+    sub = oracle.Problem(K=p.K, V=p.V, Q=p.Q, block_table=p.block_table[comp], num_blocks=p.num_blocks[comp], q_slot=p.q_slot[comp],
+                         N_max=p.N_max, keep=None if p.keep is None else p.keep[comp])
+    o_idx, o_len = oracle.select(sub, both[1].cpu().numpy())
+    assert np.array_equal(o_idx, both[2].cpu().numpy()) and np.array_equal(o_len, both[3].cpu().numpy())
