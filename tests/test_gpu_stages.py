@@ -292,3 +292,31 @@ def test_compression_beside_decode_on_two_streams():
                          N_max=p.N_max, keep=None if p.keep is None else p.keep[comp])
     o_idx, o_len = oracle.select(sub, both[1].cpu().numpy())
     assert np.array_equal(o_idx, both[2].cpu().numpy()) and np.array_equal(o_len, both[3].cpu().numpy())
+
+
+def test_largest_sequence_the_kernels_accept():
+    """Maximum size: the longest request (prefill overflow, N >> N_max) whose scores still fit on chip.  The limit is
+    found through the host-side argument check (a refused call launches nothing), then the whole protocol runs at it."""
+    c = G.ctx()
+    kw = dict(B=1, L=1, h_kv=1, G=4, d=128, b=16, N_max=5, w=64, bf16=True, heavy=8)
+    limit = None
+    for mb in range(1850, 1790, -1):
+        p = random_problem(930, num_blocks=[mb], **kw)
+        pool, batch = G.to_device(p)
+        s, _, _ = G.alloc_outputs(pool, batch)
+        try:
+            c.zp_score(pool, batch, s)
+        except binding.ZpError as e:
+            assert e.status == binding.ZP_EUNSUPPORTED
+            continue
+        limit = mb
+        break
+    c.zp_sync_status()
+    assert limit is not None and limit >= 1800, "expected about 29k positions per request to fit"
+    p.keep = np.array([[[64]]], dtype=np.int32)                     # smallest legal keep count: the window alone
+    rep = G.full_protocol(p, pool, G.to_device(p)[1])
+    assert rep["worst_rel"] < 1e-3
+    p.keep = None                                                   # the full budget: rows come from far behind their targets
+    rep = G.full_protocol(p, pool, G.to_device(p)[1])
+    assert rep["worst_rel"] < 1e-3
+    print("largest accepted request: %d blocks = %d positions" % (limit, limit * 16))
