@@ -108,8 +108,10 @@ size_t zp_scratch_bytes(const zp_pool *pool, const zp_batch *batch);
    zp_scratch_bytes reports) is SWITCHED OFF in this build and returns ZP_EUNSUPPORTED: the bounded wait between the
    workgroups of a unit has expired intermittently on MI355X and the cause is not established.
    ZP_OPT_SPIN_LIMIT: bound on that wait loop (iterations, > 0).
-   ZP_OPT_STREAMS: cap (1..8) on the ticket streams the split path orders its workgroups by. */
-typedef enum { ZP_OPT_SPLIT = 1, ZP_OPT_SPIN_LIMIT = 2, ZP_OPT_STREAMS = 3 } zp_option;
+   ZP_OPT_STREAMS: cap (1..8) on the ticket streams the split path orders its workgroups by.
+   ZP_OPT_XCD_MAP: 1 (default) = every XCD works on a contiguous range of units, so that the kv heads of one
+   (request, layer), which read the same blocks, run side by side on one XCD; 0 = workgroup i takes unit i. */
+typedef enum { ZP_OPT_SPLIT = 1, ZP_OPT_SPIN_LIMIT = 2, ZP_OPT_STREAMS = 3, ZP_OPT_XCD_MAP = 4 } zp_option;
 zp_status zp_set_option(zp_ctx *ctx, int32_t option, int32_t value);
 
 /*

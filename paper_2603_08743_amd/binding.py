@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libzp.so")
 
 ZP_OK, ZP_EINVAL, ZP_ENOMEM, ZP_EHIP, ZP_EUNSUPPORTED = 0, -1, -2, -3, -4
 ZP_F32, ZP_BF16 = 0, 1
-ZP_OPT_SPLIT, ZP_OPT_SPIN_LIMIT, ZP_OPT_STREAMS = 1, 2, 3
+ZP_OPT_SPLIT, ZP_OPT_SPIN_LIMIT, ZP_OPT_STREAMS, ZP_OPT_XCD_MAP = 1, 2, 3, 4
 
 EXPORTS = ("zp_create", "zp_destroy", "zp_last_error", "zp_scratch_bytes", "zp_score", "zp_select_topk", "zp_compact_kv",
            "zp_compress", "zp_sync_status", "zp_validate_batch", "zp_plan", "zp_set_option", "zp_decode_attention", "zp_score_ex",

@@ -21,6 +21,7 @@ struct zp_ctx {
     int split_mode;  // -1 auto, 0 never, 1 whenever the shape allows
     int spin_limit;
     int max_streams; // cap on the ticket streams of the split path
+    int xcd_map;     // workgroup -> unit map: 1 contiguous ranges per XCD, 0 identity
     int n_cu;        // compute units: every kernel here fits at least one workgroup per CU
     char err[512];
 };
@@ -53,6 +54,7 @@ extern "C" zp_status zp_create(zp_ctx **out) {
     c->split_mode = -1;
     c->spin_limit = 1 << 21;
     c->max_streams = 8;
+    c->xcd_map = 1;
     c->n_cu = 0;
     (void)hipDeviceGetAttribute(&c->n_cu, hipDeviceAttributeMultiprocessorCount, dev);
     if (c->n_cu <= 0) c->n_cu = 64;
@@ -105,6 +107,7 @@ extern "C" zp_status zp_set_option(zp_ctx *ctx, int32_t option, int32_t value) {
     if (option == ZP_OPT_SPLIT && value >= -1 && value <= 0) { ctx->split_mode = value; return ZP_OK; }
     if (option == ZP_OPT_SPIN_LIMIT && value > 0) { ctx->spin_limit = value; return ZP_OK; }
     if (option == ZP_OPT_STREAMS && value >= 1 && value <= 8) { ctx->max_streams = value; return ZP_OK; }
+    if (option == ZP_OPT_XCD_MAP && (value == 0 || value == 1)) { ctx->xcd_map = value; return ZP_OK; }
     snprintf(ctx->err, sizeof(ctx->err), "zp_set_option: unknown option %d or bad value %d", option, value);
     return ZP_EINVAL;
 }
@@ -146,6 +149,7 @@ static zp_status prepare(zp_ctx *ctx, const char *who, const zp_pool *p, const z
     for (int s = 0; s < 31; s++) if ((1 << s) == p->b) a->b_shift = s;
     a->scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)p->d));
     a->status = ctx->d_status;
+    a->xcd_map = ctx->xcd_map;
 
     *path = PATH_GENERIC;
     *NW = 4; *RB = 0;

@@ -66,6 +66,16 @@ __device__ __forceinline__ void report_bad(const Args &a, int unit, int reason) 
     }
 }
 
+// Workgroup -> unit.  The hardware deals consecutive workgroups to the 8 XCDs in turn (workgroup i runs on XCD
+// i mod 8, each with its own L2 and address-translation cache).  Neighbouring units are the kv heads of one
+// (request, layer): they walk the same physical blocks, 256 bytes apart inside every 2 KiB token row.  The map below
+// gives every XCD a contiguous range of units, so that those neighbours run side by side on one XCD.
+__device__ __forceinline__ int unit_of_block(int bid, int n, int mode) {
+    if (mode == 0 || n < 16) return bid;
+    const int q = n >> 3, r = n & 7, x = bid & 7, i = bid >> 3;
+    return x < r ? x * (q + 1) + i : r * (q + 1) + (x - r) * q + i;
+}
+
 // Decode the unit and check its scalar metadata (identical for every thread and every workgroup
 // that looks at the unit).  Returns 0 or the reason the unit must be skipped.
 __device__ inline int unit_scalars(const Args &a, int unit, Unit &u) {

@@ -42,6 +42,7 @@ struct Args {
     int G, T_max, budget, row_bytes, b_shift;   // b_shift >= 0 iff b is a power of two
     float scale_log2;                          // log2(e) / sqrt(d)
     int stages;
+    int xcd_map;                               // 1: contiguous unit ranges per XCD (see unit_of_block)
     // staged inputs / outputs (device pointers, any may be null depending on stages)
     const float *scores_in; int scores_in_stride;
     float *scores_out;                         // [units][T_max]

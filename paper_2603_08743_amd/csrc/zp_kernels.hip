@@ -84,7 +84,7 @@ __global__ void __launch_bounds__(256) unit_generic(const Args a) {
     int *tbl = (int *)(smem + a.off_tbl), *dst = (int *)(smem + a.off_dst);
     Misc *misc = (Misc *)(smem + a.off_misc);
     Unit u;
-    if (!unit_setup(a, blockIdx.x, u, tbl, dst, misc)) return;
+    if (!unit_setup(a, unit_of_block((int)blockIdx.x, (int)gridDim.x, a.xcd_map), u, tbl, dst, misc)) return;
     if (a.stages & STAGE_SCORE) score_generic<DT>(a, u, smem, tbl);
     unit_tail<0, DT>(a, u, smem, tbl, dst, misc);
 }

@@ -30,7 +30,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW
     int *tbl = (int *)(smem + a.off_tbl), *dst = (int *)(smem + a.off_dst);
     Misc *misc = (Misc *)(smem + a.off_misc);
     Unit u;
-    if (!unit_setup(a, blockIdx.x, u, tbl, dst, misc)) return;
+    if (!unit_setup(a, unit_of_block((int)blockIdx.x, (int)gridDim.x, a.xcd_map), u, tbl, dst, misc)) return;
 
     using KTl = KTile<D>;
     constexpr int NT = NW * 64, KK = D / 16, LPT = KT * KTl::CPR / NT;

@@ -1,5 +1,5 @@
 // Stand-alone driver for hardware-counter runs of the fused compression kernel (no Python, no torch):
-//   rocprofv3 --pmc FETCH_SIZE -- ./zp_prof_driver [B] [L_slab] [config] [reps] [stages] [split] [streams] [extras]
+//   rocprofv3 --pmc FETCH_SIZE -- ./zp_prof_driver [B] [L_slab] [config] [reps] [stages] [split] [streams] [extras] [xcd_map]
 // stages = 1 also times the staged calls (zp_score, zp_select_topk, zp_compact_kv) one by one.
 // extras: bit mask of score refinements to time with zp_compress_ex after the plain run (1 global score, 2 max
 // pooling with kernel 7, 4 lightning redundancy); every set of bits from 1 up to the mask that is a subset of it is run.
@@ -62,6 +62,7 @@ int main(int argc, char **argv) {
     const int split = argc > 6 ? atoi(argv[6]) : -1;
     const int streams = argc > 7 ? atoi(argv[7]) : 8;
     const int extras = argc > 8 ? atoi(argv[8]) : 0;
+    const int xcd_map = argc > 9 ? atoi(argv[9]) : 1;
     int h_kv = 8, h_q = 32, d = 128, b = 16, N_max = 257, w = 64;
     bool per_head_keep = true;
     if (cfg == 1) { h_kv = 4; h_q = 28; N_max = 129; w = 32; per_head_keep = false; }
@@ -104,6 +105,7 @@ int main(int argc, char **argv) {
     if (zp_create(&ctx) != ZP_OK) { fprintf(stderr, "%s\n", zp_last_error(nullptr)); return 1; }
     zp_set_option(ctx, ZP_OPT_SPLIT, split);
     zp_set_option(ctx, ZP_OPT_STREAMS, streams);
+    zp_set_option(ctx, ZP_OPT_XCD_MAP, xcd_map);
     zp_pool pool = {K, V, Q, 0, Ls, N_total, b, h_kv, h_q, d, B, w, ZP_BF16};
     zp_batch batch = {B, N_max, N_max, Ls, d_tbl, nullptr, d_nb, d_slot, nullptr, d_keep};
     hipEvent_t e0, e1;

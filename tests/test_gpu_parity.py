@@ -141,3 +141,22 @@ def test_logit_spike_late_in_the_sequence():
     pool, batch = G.to_device(p)
     rep = G.full_protocol(p, pool, batch)
     assert rep["worst_rel"] < 1e-3
+
+
+def test_workgroup_to_unit_map_does_not_change_results():
+    # 21 units: not a multiple of the 8 XCDs, so the ragged branch of the map is exercised; both maps must give the same bits
+    p = random_problem(600, B=3, L=1, h_kv=7, G=4, d=128, b=16, N_max=6, w=16, extra_blocks=1, bf16=True, heavy=4)
+    rng = np.random.default_rng(0)
+    p.keep = rng.integers(16, 81, size=(3, 1, 7)).astype(np.int32)
+    pool, batch = G.to_device(p)
+    outs = []
+    for mode in (0, 1):
+        G.ctx().zp_set_option(binding.ZP_OPT_XCD_MAP, mode)
+        pl = G.clone_pool(pool)
+        s, i, l = G.run_fused(pl, batch)
+        outs.append((s, i, l, pl.k, pl.v))
+    G.ctx().zp_set_option(binding.ZP_OPT_XCD_MAP, 1)
+    for a, c in zip(*outs):
+        assert torch.equal(a.view(torch.int16) if a.dtype == torch.bfloat16 else a, c.view(torch.int16) if c.dtype == torch.bfloat16 else c)
+    rep = G.full_protocol(p, pool, batch)
+    assert rep["worst_rel"] < 1e-3
