@@ -239,8 +239,10 @@ __device__ inline void select_unit(const Args &a, const Unit &u, unsigned *keys,
 // Compaction (appendix "KV Cache Compression"): row r of the targets <- source row list[r], K and V.
 // Safe in place: kept positions ascend, so list[r] >= r; ranks are taken in ascending chunks, every
 // row of a chunk is in registers (loads complete) before the barrier that precedes the chunk's
-// stores, and a later chunk only reads positions at or beyond its own ranks, so its loads may be in
-// flight while the previous chunk is being stored (two register sets, loads and stores overlap).
+// stores, and a later chunk only reads positions at or beyond its own ranks, so its loads may be
+// issued while the previous chunk's stores are still on their way.  One register set: what makes this
+// phase fast is the number of waves per CU that issue memory operations, not the rows a thread holds
+// (a second, alternating set cost registers, i.e. resident waves, and was slower).
 template <int U, int FM> struct RowSet {   // FM: 0 K/V only, 1 F read back from global memory, 2 F from the on-chip copy
     u32x4 kk[U], vv[U];
     size_t dof[U];
@@ -295,19 +297,13 @@ __device__ inline void compact_unit(const Args &a, const Unit &u, const int *tbl
     const bool active = rsub < rpp;
     constexpr int U = ZP_COMPACT_U;
     const int CH = U * rpp;                                      // rows per chunk
-    RowSet<U, FM> A, B;
-    if (k > 0) rows_load<U, FM>(a, u, tbl, dst, list, Sg, k, 0, rpp, rsub, ch, active, A);
+    RowSet<U, FM> A;
 #pragma unroll 1
-    for (int r0 = 0; r0 < k; r0 += 2 * CH) {
+    for (int r0 = 0; r0 < k; r0 += CH) {
+        rows_load<U, FM>(a, u, tbl, dst, list, Sg, k, r0, rpp, rsub, ch, active, A);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        if (r0 + CH < k) rows_load<U, FM>(a, u, tbl, dst, list, Sg, k, r0 + CH, rpp, rsub, ch, active, B);
         rows_store<U, FM>(a, ch, A);
-        if (r0 + CH >= k) break;
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (r0 + 2 * CH < k) rows_load<U, FM>(a, u, tbl, dst, list, Sg, k, r0 + 2 * CH, rpp, rsub, ch, active, A);
-        rows_store<U, FM>(a, ch, B);
     }
 }
 

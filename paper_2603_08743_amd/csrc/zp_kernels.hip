@@ -110,7 +110,7 @@ static void pick_geometry(int NB, int *NW, int *RB) {
     if (NB <= 1) { *NW = 1; *RB = 1; }
     else if (NB <= 2) { *NW = 2; *RB = 1; }
     else if (NB <= 4) { *NW = 4; *RB = 1; }
-    else if (NB <= 8) { *NW = 4; *RB = 2; }
+    else if (NB <= 8) { *NW = 8; *RB = 1; }
     else if (NB <= 16) { *NW = 8; *RB = 2; }
     else if (NB <= 24) { *NW = 8; *RB = 3; }
     else { *NW = 8; *RB = 4; }
