@@ -5,7 +5,7 @@
 #include "zp_kernels.h"
 
 #ifndef ZP_COMPACT_U
-#define ZP_COMPACT_U 8
+#define ZP_COMPACT_U 4
 #endif
 
 namespace zp {
