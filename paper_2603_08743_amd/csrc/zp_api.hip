@@ -248,8 +248,12 @@ static zp_status launch(zp_ctx *ctx, const char *who, zp::Args &a, Path path, in
         a.partial = (float2 *)(ctx->scratch + l.off_partial);
         a.lse_g = (float *)(ctx->scratch + l.off_lse);
         a.sbuf = (float *)(ctx->scratch + l.off_sbuf);
+#ifdef ZP_WITH_SPLIT
         e = zp::launch_zero_words(a.sync, 256 + 3 * units, (hipStream_t)stream);
         if (e == hipSuccess) e = zp::launch_unit_split(a, units, NW, RB, (hipStream_t)stream);
+#else   /* the split kernel is not part of this build (switched off, see zp_set_option); split_mode can never be 1 */
+        e = hipErrorNotSupported;
+#endif
     } else
     e = path == PATH_MFMA ? zp::launch_unit_mfma(a, units, NW, RB, (hipStream_t)stream)
                           : zp::launch_unit_generic(a, units, (hipStream_t)stream);
