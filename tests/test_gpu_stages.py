@@ -320,3 +320,33 @@ def test_largest_sequence_the_kernels_accept():
     rep = G.full_protocol(p, pool, G.to_device(p)[1])
     assert rep["worst_rel"] < 1e-3
     print("largest accepted request: %d blocks = %d positions" % (limit, limit * 16))
+
+
+def test_fused_call_inside_a_hip_graph():
+    """zp_compress allocates nothing and records only kernels, so a caller can capture it in a HIP graph: every replay
+    (with eager work and synchronisations of the program in between) must give the bits of the eager call."""
+    w = workloads.config(2, B=2, L=1, N_total=600)
+    _, pool, batch = G.workload_problem(w)
+    c = G.ctx()
+    K0, V0 = pool.k.clone(), pool.v.clone()
+    s_e, i_e, l_e = G.run_fused(pool, batch)                          # eager (also the warm-up the capture needs)
+    Ke, Ve = pool.k.clone(), pool.v.clone()
+    s_g, i_g, l_g = G.alloc_outputs(pool, batch)
+    graph = torch.cuda.CUDAGraph()
+    pool.k.copy_(K0)
+    pool.v.copy_(V0)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):
+        c.zp_compress(pool, batch, l_g, s_g, i_g)
+    for rep in range(3):
+        pool.k.copy_(K0)
+        pool.v.copy_(V0)
+        s_g.fill_(float("nan"))
+        i_g.fill_(-7)
+        l_g.fill_(-7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        c.zp_sync_status()
+        assert torch.equal(s_g.view(torch.int32), s_e.view(torch.int32)) and torch.equal(i_g, i_e) and torch.equal(l_g, l_e), "replay %d" % rep
+        assert torch.equal(pool.k.view(torch.int16), Ke.view(torch.int16)) and torch.equal(pool.v.view(torch.int16), Ve.view(torch.int16)), "replay %d" % rep
