@@ -30,7 +30,7 @@ def log(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
 
 
-def algorithmic_bytes(w, keep_idx, slab_layers, layer0):
+def algorithmic_bytes(w, keep_idx, slab_layers, layer0, tbl=None, dst=None):
     """Bytes the method itself must move for one slab launch: K rows read for scoring, the window queries,
     K and V rows that change place (read + write), both block tables.  No second key sweep, no debug output."""
     import torch
@@ -39,7 +39,13 @@ def algorithmic_bytes(w, keep_idx, slab_layers, layer0):
     T_live = int(w.num_blocks.sum()) * w.b * slab_layers * w.h_kv          # valid_len is None in the bench configs
     k = keep_idx.shape[-1]
     ar = torch.arange(k, device=keep_idx.device, dtype=torch.int32)
-    moved = int(((keep_idx >= 0) & (keep_idx != ar)).sum().item())         # in place: row r moves iff its source position differs
+    if dst is None:
+        moved = int(((keep_idx >= 0) & (keep_idx != ar)).sum().item())     # in place: row r moves iff its source position differs
+    else:                                                                   # separate targets: also when the block differs
+        ki = keep_idx.view(w.B, -1, k)
+        src_blk = torch.gather(tbl.long()[:, None, :].expand(-1, ki.shape[1], -1), 2, (ki.clamp(min=0) // w.b).long())
+        dst_blk = dst.long()[:, (ar // w.b).long()][:, None, :]
+        moved = int(((ki >= 0) & ((src_blk != dst_blk) | (ki % w.b != ar % w.b))).sum().item())
     kept = int((keep_idx >= 0).sum().item())
     table = int(w.num_blocks.sum()) * 4 * slab_layers * w.h_kv + units * (w.N_max - 1) * 4
     total = T_live * row + units * (w.h_q // w.h_kv) * w.w * row + 4 * moved * row + table
@@ -51,7 +57,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", type=int, default=2, help="workload: index into the benchmark configurations (1, 2 or 4)")
+    ap.add_argument("--config", type=int, default=2, help="workload: index into the benchmark configurations (1, 2, 3 or 4)")
+    ap.add_argument("--compress-frac", type=float, default=1.0, help="config 3 only: fraction of the 512 requests that compress in this step")
     ap.add_argument("--slab-layers", type=int, default=8, help="layers per zp_compress launch (layer stride)")
     ap.add_argument("--batch", type=int, default=None, help="override the number of compressing requests (smaller pool too)")
     ap.add_argument("--cpu-sample-requests", type=int, default=6, help="requests (x one slab of layers) the oracle is timed on; 0 = skip")
@@ -75,7 +82,9 @@ def main():
     dev = torch.device("cuda:0")
     ctx = binding.Context()
 
-    if args.batch is None:
+    if args.config == 3:
+        w = workloads.config(3, B=args.batch, compress_frac=args.compress_frac)
+    elif args.batch is None:
         w = workloads.config(args.config)
     else:   # reduced batch: same per-unit shape, a pool just large enough
         N_max = workloads.config(args.config, B=1, L=1, N_total=2048).N_max
@@ -95,7 +104,16 @@ def main():
     keep = None if w.keep is None else torch.from_numpy(w.keep).to(dev)
     units = w.B * Ls * w.h_kv
     len_out = torch.empty(units, dtype=torch.int32, device=dev)
-    batch = binding.Batch(block_table=tbl, num_blocks=nb, q_slot=slot, N_max=w.N_max, L=w.L, keep=keep)
+    dst = None
+    plan_ms = None
+    if args.config == 3:   # shared prefix blocks are never written: the host planner redirects them to fresh blocks
+        refcnt = w.refcnt.copy()
+        t0 = time.time()
+        plan = binding.zp_plan(w.block_table, w.num_blocks, w.N_max, refcnt, w.free_list)
+        plan_ms = (time.time() - t0) * 1e3
+        dst = torch.from_numpy(plan["dst_table"]).to(dev)
+        log("zp_plan (host): %.2f ms, %d fresh blocks, %d blocks freed" % (plan_ms, plan["n_free_used"], len(plan["freed"])))
+    batch = binding.Batch(block_table=tbl, num_blocks=nb, q_slot=slot, N_max=w.N_max, L=w.L, keep=keep, dst_table=dst)
     pools = [binding.Pool(k=K, v=V, q=Q, layer0=s * Ls) for s in range(n_slabs)]
 
     refine = [x for x in args.refine.split(",") if x]
@@ -156,7 +174,7 @@ def main():
     sample = list(range(min(args.cpu_sample_requests, w.B)))
     compress(pools[0], len_out, None, keep_idx)
     ctx.zp_sync_status()
-    bytes_launch, moved, kept, T_live = algorithmic_bytes(w, keep_idx, Ls, 0)
+    bytes_launch, moved, kept, T_live = algorithmic_bytes(w, keep_idx, Ls, 0, tbl, dst)
     entries_step = int(w.num_blocks.sum()) * w.b * w.L * w.h_kv
     req_tokens_step = int(w.num_blocks.sum()) * w.b
     value = entries_step / (ms_per_step * 1e-3)
@@ -209,7 +227,7 @@ def main():
             tot = len(sample) * Ls * w.h_kv
             cpu["kept_sets_equal_to_oracle"] = "%d/%d units" % (same, tot)
             Kc = to_host_bits(K[:, idt])
-            if same == tot:
+            if same == tot and dst is None:
                 assert np.array_equal(Kc, prob.K), "compacted K differs from the oracle on the sampled requests"
                 cpu["compacted_bytes_equal"] = True
         log("oracle: %.3g entries/s on %d threads (%s)" % (cpu["value"], cpu["cores"], cpu["sample"]))
@@ -268,7 +286,7 @@ def main():
         "config": {"workload": w.name, "B": w.B, "L": w.L, "h_kv": w.h_kv, "h_q": w.h_q, "d": w.d, "b": w.b, "N_max": w.N_max, "w": w.w,
                    "budget": w.budget, "pool_blocks": w.N_total, "layers_per_launch": Ls, "launches_per_step": n_slabs,
                    "keep": "per-head uniform [1024,4096]" if args.config == 2 else ("per-head" if w.keep is not None else "budget"),
-                   "refinements": refine},
+                   "refinements": refine, "compress_frac": args.compress_frac if args.config == 3 else None, "plan_host_ms": plan_ms},
         "request_tokens_per_s": req_tokens_step / (ms_per_step * 1e-3),
         "wall_ms_per_step_incl_restore": wall * 1e3 / args.steps,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
