@@ -167,7 +167,9 @@ static zp_status prepare(zp_ctx *ctx, const char *who, const zp_pool *p, const z
         if (ex->lambda != 0.f && !(ex->tau > 0.f && std::isfinite(ex->tau))) return fail(ctx, ZP_EINVAL, "%s: tau must be positive", who);
         if (ex->F && (long long)p->L_slab * p->N_total * p->b * p->h_kv > 0xffffffffLL)
             return fail(ctx, ZP_EUNSUPPORTED, "%s: global-score cache of more than 2^32-1 entries per slab", who);
-        if (ex->F) a->ex |= zp::EX_GLOBAL | (fused ? zp::EX_MOVE_F_LDS : 0);
+        // the fused call moves the cached global scores with the rows: from an on-chip copy when targets differ from
+        // sources (blocks may be shared inside the batch), read back from F otherwise (in place: every block is private)
+        if (ex->F) a->ex |= zp::EX_GLOBAL | (fused ? (b->dst_table ? zp::EX_MOVE_F_LDS : zp::EX_MOVE_F) : 0);
         if (ex->pool_kernel > 1) a->ex |= zp::EX_POOL | (ex->pool_first_only ? zp::EX_POOL_FIRST : 0);
         if (ex->lambda != 0.f) a->ex |= zp::EX_RED;
         a->F = ex->F; a->compressed = ex->compressed; a->alpha = ex->alpha; a->lambda = ex->lambda; a->p_thr = ex->p;
@@ -175,6 +177,7 @@ static zp_status prepare(zp_ctx *ctx, const char *who, const zp_pool *p, const z
         a->pool_r = ex->pool_kernel / 2;
     }
     const bool red_mfma = *path == PATH_MFMA && a->b_shift >= 0 && p->b <= 32;
+    if ((a->ex & zp::EX_RED) && *path == PATH_MFMA && p->b == 16 && *RB == 1) a->ex |= zp::EX_RED_FUSED;   // similarity tiles from sweep 2's key tiles
     const size_t refine_bytes = !a->ex ? 0 : ((a->ex & (zp::EX_POOL | zp::EX_RED)) ? (size_t)a->T_max * 4 : 0) +
                                 ((a->ex & zp::EX_RED) ? (red_mfma ? (size_t)*NW * 96 * 4 : (size_t)a->T_max * 12) : 0);
     const size_t list_bytes = (size_t)a->budget * 4;
@@ -214,7 +217,8 @@ static zp_status prepare(zp_ctx *ctx, const char *who, const zp_pool *p, const z
     size_t union_bytes = score_bytes > list_bytes ? score_bytes : list_bytes;
     if (refine_bytes > union_bytes) union_bytes = refine_bytes;
     a->off_G = a->off_union + align16((int)union_bytes);
-    const size_t total = (size_t)a->off_G + ((a->ex & zp::EX_MOVE_F_LDS) ? (size_t)a->T_max * 4 : 0);
+    a->off_R = a->off_G + ((a->ex & zp::EX_MOVE_F_LDS) ? align16(a->T_max * 4) : 0);
+    const size_t total = (size_t)a->off_R + ((a->ex & zp::EX_RED_FUSED) ? (size_t)a->T_max * 4 + (size_t)*NW * 96 * 4 : 0);
     if (total > (size_t)kLdsLimit)
         return fail(ctx, ZP_EUNSUPPORTED, "%s: %zu bytes of LDS per unit exceed %d (max_blocks*b too large)", who, total, kLdsLimit);
     a->lds_bytes = (int)align16((int)total);

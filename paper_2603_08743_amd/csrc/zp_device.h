@@ -401,8 +401,9 @@ __device__ inline void redundancy_valu(const Args &a, const Unit &u, const int *
 // Lane L, register i holds the entry (row 8*(i/4) + 4*(L/32) + i%4, column L%32); only entries whose row and
 // column lie in the same block are used.  A wave owns a group; its 96 words of LDS hold the inverse norms and
 // the (row, value) of the entry zeroed in every column.
+// last_only: only the rows of the last block are produced (the live prefix was done from the key tiles of sweep 2).
 template <int D>
-__device__ inline void redundancy_mfma(const Args &a, const Unit &u, const int *tbl, float *rs, float *wave_scratch) {
+__device__ inline void redundancy_mfma(const Args &a, const Unit &u, const int *tbl, float *rs, float *wave_scratch, bool last_only) {
     constexpr int KK = D / 16;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, nw = blockDim.x >> 6, l32 = lane & 31, hf = lane >> 5;
     float *inv = wave_scratch + wv * 96, *zv = inv + 64;
@@ -416,12 +417,13 @@ __device__ inline void redundancy_mfma(const Args &a, const Unit &u, const int *
     // groups of this wave in ascending order, wholly stale ones skipped; the fragments of the next group are
     // requested before the current one is worked on
     auto next_group = [&](int g) {
-        while (g < ngroups && g * 32 >= u.vl && g * 32 + 32 <= stale_hi) g += nw;
+        while (g < ngroups && g * 32 + 32 <= stale_hi && (last_only || g * 32 >= u.vl)) g += nw;
         return g;
     };
     auto live_of = [&](int g) {
         const int p = g * 32 + l32;
-        return p < u.T ? pos_to_live(u, a, p) : -1;
+        if (p >= u.T || (last_only && p < stale_hi)) return -1;
+        return pos_to_live(u, a, p);
     };
     auto load_group = [&](int g, bf16x8 (&kf)[KK]) {
         const int pc = live_of(g) >= 0 ? g * 32 + l32 : u.T - 1;  // rows that are not live read a valid row and are masked
@@ -485,6 +487,69 @@ __device__ inline void redundancy_mfma(const Args &a, const Unit &u, const int *
     __syncthreads();
 }
 
+// Block size 16, live prefix: the similarity matrix of one block from the key tile that sweep 2 holds in LDS anyway
+// (rows `rows`, ROWB bytes apart, 16 keys of one block).  K_blk K_blk^T is one 16x16 tile of the matrix cores
+// (v_mfma_f32_16x16x32_bf16, both operands the same fragments: lane L supplies key L%16, elements 8*(L/16).. of every
+// 32-wide step; register i of lane L holds entry (row 4*(L/16) + i, column L%16)).  j_first: live index of the
+// block's first key; rows at or beyond the live prefix are not live.  scratch: 48 words of LDS of this wave.
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+template <int D, int ROWB>
+__device__ __forceinline__ void block_row_sums_lds(const Args &a, const Unit &u, const char *rows, int j_first, float inv_len, float *rs,
+                                                   float *scratch, int lane) {
+    const int c = lane & 15, g = lane >> 4;
+    float *inv = scratch, *zv = scratch + 32;
+    int *zr = (int *)(scratch + 16);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    const char *kp = rows + c * ROWB + g * 16;
+#pragma unroll
+    for (int kk = 0; kk < D / 32; kk++) {
+        const bf16x8 f = *(const bf16x8 *)(kp + kk * 64);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f, f, acc, 0, 0, 0);
+    }
+    const bool live_c = j_first + c < u.vl;
+    const int di = c - 4 * g;                                   // register with the diagonal entry, if it is in this lane
+    float dg = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; i++) dg = i == di ? acc[i] : dg;
+    if (di >= 0 && di < 4) inv[c] = (live_c && dg > 0.f) ? 1.0f / sqrtf(dg) : 0.f;
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");           // LDS serves a wave's accesses in order
+    const float ic = inv[c];
+    float csum = 0.f, lastv = 0.f;
+    int last = -1;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const int row = 4 * g + i;
+        const float ir = inv[row];
+        float val = 0.f;
+        if (row != c && ir != 0.f && ic != 0.f) val = acc[i] * (ir * ic);
+        csum += val;
+        if (val > a.p_thr) { last = row; lastv = val; }           // rows ascend with i
+    }
+    // the four lanes of a column (rows 0-3, 4-7, 8-11, 12-15) combine: column sum in row order, last entry above p
+    float s1 = __shfl_xor(csum, 16);
+    float lo = g & 1 ? s1 : csum, hi = g & 1 ? csum : s1;       // (rows of the even group) + (rows of the odd group)
+    const float pair = lo + hi;
+    const float opair = __shfl_xor(pair, 32);
+    const float colsum = g & 2 ? opair + pair : pair + opair;    // same bits in all four lanes
+#pragma unroll
+    for (int off = 16; off <= 32; off <<= 1) {
+        const int ol = __shfl_xor(last, off);
+        const float ov = __shfl_xor(lastv, off);
+        if (ol > last) { last = ol; lastv = ov; }
+    }
+    if (g == 0) { zr[c] = last; zv[c] = lastv; }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (g == 0 && live_c) {                                      // symmetric: row sum of key c = its column sum, minus what was zeroed in row c
+        float corr = 0.f;
+#pragma unroll
+        for (int cc = 0; cc < 16; cc++)
+            if (zr[cc] == c) corr += zv[cc];
+        rs[j_first + c] = (colsum - corr) * inv_len;
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");           // the next block reuses the wave's scratch
+}
+
 // D > 0: called from the matrix-core kernel for head dimension D (bf16); D = 0: generic kernel, element type DT.
 template <int D, int DT>
 __device__ inline void refine_unit(const Args &a, const Unit &u, char *smem, const int *tbl, Misc *misc) {
@@ -526,8 +591,11 @@ __device__ inline void refine_unit(const Args &a, const Unit &u, char *smem, con
     }
     if (a.ex & EX_RED) {
         const bool mf = D > 0 && 32 % a.b == 0;
-        if (mf) {
-            if constexpr (D > 0) redundancy_mfma<D>(a, u, tbl, tmp, tmp + a.T_max);
+        if (a.ex & EX_RED_FUSED) {                               // the live prefix was done from the key tiles of sweep 2
+            tmp = (float *)(smem + a.off_R);
+            if constexpr (D > 0) redundancy_mfma<D>(a, u, tbl, tmp, tmp + a.T_max, true);
+        } else if (mf) {
+            if constexpr (D > 0) redundancy_mfma<D>(a, u, tbl, tmp, tmp + a.T_max, false);
         } else {
             redundancy_valu<DT>(a, u, tbl, tmp, tmp + a.T_max, (int *)(tmp + 2 * (size_t)a.T_max), tmp + 3 * (size_t)a.T_max);
         }

@@ -22,6 +22,7 @@ enum : int {
     EX_RED = 4,        // S - lambda * R
     EX_MOVE_F = 8,     // compaction moves F rows read back from global memory (staged call)
     EX_POOL_FIRST = 32,  // pooling only for requests without history
+    EX_RED_FUSED = 64,   // redundancy: the similarity tiles of the live prefix come from the key tiles of sweep 2 (row sums at off_R)
     EX_MOVE_F_LDS = 16 // compaction writes the kept entries' values from the on-chip copy made by EX_GLOBAL (fused call)
 };
 
@@ -57,6 +58,7 @@ struct Args {
     float alpha, lambda, inv_tau_log2, p_thr;  // inv_tau_log2 = log2(e) / tau
     int pool_r;                                // pooling radius (kernel - 1) / 2
     int off_G;                                 // LDS: [T_max] copy of the global scores for EX_MOVE_F_LDS
+    int off_R;                                 // LDS: [T_max] redundancy row sums + 96 words per wave for EX_RED_FUSED
     // byte offsets into dynamic LDS
     int off_S, off_tbl, off_dst, off_misc, off_union, lds_bytes;
     // MFMA path geometry

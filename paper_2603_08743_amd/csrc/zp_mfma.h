@@ -30,7 +30,9 @@ template <int D> struct KTile {
     static constexpr int CPR = D * 2 / 16;        // 16-byte pieces per key row
 };
 
-template <int D, int RB, int NW, int GT>
+// RED: the launch computes the lightning redundancy with block size 16 and takes the similarity tiles of the live
+// prefix from the key tiles of sweep 2 (instantiated for RB = 1 only; otherwise the keys are read a third time in the tail).
+template <int D, int RB, int NW, int GT, bool RED>
 __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ZP_WPE(NW, RB)))) unit_mfma(const Args a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     int *tbl = (int *)(smem + a.off_tbl), *dst = (int *)(smem + a.off_dst);
@@ -246,9 +248,22 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ZP
             if (hf == 0) pt[wv * KT + sub * 32 + l32] = ps;
         }
     };
+    // Redundancy (RED, b = 16): a tile holds four blocks of the live prefix; they go to four waves (alternating between
+    // the two halves of an eight-wave workgroup from tile to tile).  The last block, which sits off the 16-grid of the
+    // live sequence, is done in the tail.
+    float *rs_red = (float *)(smem + a.off_R);
+    const float inv_len = 1.0f / (float)u.Tv;
+    auto gram_tile = [&](const char *buf, int j0) {
+        constexpr int GRP = NW >= 4 ? NW / 4 : 1, STEP = NW >= 4 ? 4 : NW;
+        if (NW >= 4 && (j0 / KT) % GRP != wv / 4) return;
+        for (int q = wv % 4; q < KT / 16; q += STEP)
+            if (j0 + 16 * q < u.vl)
+                block_row_sums_lds<D, KTl::ROW>(a, u, buf + 16 * q * KTl::ROW, j0 + 16 * q, inv_len, rs_red, rs_red + a.T_max + wv * 96, lane);
+    };
     auto sweep2_tile = [&](const char *buf, float *pt, int j0) {
         if (j0 + KT > u.Tv - w) sweep2_body(buf, pt, j0, std::true_type());
         else sweep2_body(buf, pt, j0, std::false_type());
+        if (RED) gram_tile(buf, j0);
     };
     auto reduce_tile = [&](const float *pt, int j0) {         // fixed-order sum over the waves: deterministic
         if (tid < KT) {
@@ -290,12 +305,20 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ZP
 template <int D, int RB, int NW>
 static hipError_t launch_g(const Args &a, int units, hipStream_t s) {
     const dim3 grid(units), block(NW * 64);
-#define ZP_LAUNCH(GT)                                                                        \
-    {                                                                                        \
-        hipError_t e = allow_big_lds(unit_mfma<D, RB, NW, GT>);                              \
-        if (e != hipSuccess) return e;                                                       \
-        hipLaunchKernelGGL((unit_mfma<D, RB, NW, GT>), grid, block, a.lds_bytes, s, a);      \
-    }                                                                                        \
+#define ZP_LAUNCH(GT)                                                                                  \
+    {                                                                                                  \
+        if constexpr (RB == 1) {                                                                       \
+            if (a.ex & EX_RED_FUSED) {                                                                 \
+                hipError_t e = allow_big_lds(unit_mfma<D, RB, NW, GT, true>);                          \
+                if (e != hipSuccess) return e;                                                         \
+                hipLaunchKernelGGL((unit_mfma<D, RB, NW, GT, true>), grid, block, a.lds_bytes, s, a);  \
+                break;                                                                                 \
+            }                                                                                          \
+        }                                                                                              \
+        hipError_t e = allow_big_lds(unit_mfma<D, RB, NW, GT, false>);                                 \
+        if (e != hipSuccess) return e;                                                                 \
+        hipLaunchKernelGGL((unit_mfma<D, RB, NW, GT, false>), grid, block, a.lds_bytes, s, a);         \
+    }                                                                                                  \
     break;
 #ifdef ZP_DEV_FAST   /* development builds: only the instantiation of the 8B-like benchmark shape */
     switch (a.G) {

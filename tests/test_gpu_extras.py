@@ -215,6 +215,8 @@ def test_refinements_with_stale_gaps_fp32():
     (1, 40, 64, 16, 9, 2, True),        # window longer than a block
     (4, 16, 128, 64, 3, 1, True),       # block size off the matrix-core menu: vector-ALU redundancy inside the MFMA kernel
     (5, 32, 64, 4, 30, 3, True),
+    (4, 32, 128, 16, 8, 1, True),       # four waves: the tile's four blocks go to one wave each
+    (2, 8, 64, 16, 5, 1, True),         # a single wave takes all four blocks of a tile
 ])
 @pytest.mark.parametrize("first_only", [False, True], ids=["pool-always", "pool-first"])
 def test_refinements_bf16(Gq, w, d, b, N_max, extra, gaps, first_only):
