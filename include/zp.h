@@ -97,10 +97,9 @@ zp_status zp_create(zp_ctx **out);
 void zp_destroy(zp_ctx *ctx);
 const char *zp_last_error(const zp_ctx *ctx); /* ctx may be NULL: text of the last failed zp_create/zp_plan */
 
-/* Device scratch zp_score / zp_compress need beyond inputs and outputs for this shape when ZP_OPT_SPLIT
-   is 1: exchange buffers between the workgroups that share a unit (0 if the shape cannot be split).
-   The context allocates it on the first call that needs more than it holds and keeps it; calls
-   on one context must therefore not overlap on different streams. */
+/* Device scratch zp_score / zp_compress need beyond inputs and outputs for this shape.  The kernels of this build keep
+   everything between their steps on chip, so this is 0; it is non-zero only for the switched-off split kernel (see
+   ZP_OPT_SPLIT), whose exchange buffers the context would allocate on first use and keep. */
 size_t zp_scratch_bytes(const zp_pool *pool, const zp_batch *batch);
 
 /* Tuning / test switches.  ZP_OPT_SPLIT: -1 automatic (default) and 0 = one workgroup per unit (keys swept twice
