@@ -61,7 +61,7 @@ def main():
     ap.add_argument("--compress-frac", type=float, default=1.0, help="config 3 only: fraction of the 512 requests that compress in this step")
     ap.add_argument("--slab-layers", type=int, default=8, help="layers per zp_compress launch (layer stride)")
     ap.add_argument("--batch", type=int, default=None, help="override the number of compressing requests (smaller pool too)")
-    ap.add_argument("--cpu-sample-requests", type=int, default=6, help="requests (x one slab of layers) the oracle is timed on; 0 = skip")
+    ap.add_argument("--cpu-sample-requests", type=int, default=32, help="requests (x one slab of layers) the oracle is timed on; 0 = skip")
     ap.add_argument("--no-check", action="store_true", help="skip comparing the sampled requests with the oracle")
     ap.add_argument("--beside-decode", type=int, default=0, metavar="REQUESTS", help="also time one slab launch while a paged decode-attention "
                     "load over this many other requests runs on a second stream (asynchronous compression); adds 'beside_decode' to the line")
