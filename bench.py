@@ -57,7 +57,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", type=int, default=2, help="workload: index into the benchmark configurations (1, 2, 3 or 4)")
+    ap.add_argument("--config", type=int, default=2, help="workload: index into the benchmark configurations (1, 2, 3 or 4); 5 = the paper's own geometry (b=256, w=16)")
     ap.add_argument("--compress-frac", type=float, default=1.0, help="config 3 only: fraction of the 512 requests that compress in this step")
     ap.add_argument("--slab-layers", type=int, default=8, help="layers per zp_compress launch (layer stride)")
     ap.add_argument("--batch", type=int, default=None, help="override the number of compressing requests (smaller pool too)")

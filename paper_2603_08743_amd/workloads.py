@@ -243,7 +243,8 @@ _BASE_SEED = 20260308
 
 def config(i: int, *, B: Optional[int] = None, L: Optional[int] = None, N_total: Optional[int] = None,
            compress_frac: float = 1.0) -> Workload:
-    """The five benchmark configurations (B, L, N_total may be reduced for parity tests; shapes per unit stay real)."""
+    """The five benchmark configurations (B, L, N_total may be reduced for parity tests; shapes per unit stay real), and as
+    number 5 the geometry of the paper's own runs (experimental setup: block size 256, window 16)."""
     seed = _BASE_SEED + i
     if i == 0:   # tiny fp32 case: 16 cached tokens, budget 12
         return make_workload("cfg0-tiny-f32", L=1, h_kv=2, h_q=4, d=64, dtype="f32", b=4, N_max=4, w=2, B=1,
@@ -269,4 +270,8 @@ def config(i: int, *, B: Optional[int] = None, L: Optional[int] = None, N_total:
         return make_workload("cfg4-14b-budget8192", L=48 if L is None else L, h_kv=8, h_q=40, d=128, dtype="bf16", b=16,
                              N_max=513, w=128, B=Bv, N_total=(65792 if N_total is None else N_total), seed=seed,
                              keep_range=(2048, 8192))
-    raise ValueError("config index must be 0..4")
+    if i == 5:   # the geometry the paper itself runs (block size 256, window 16), budget 2048, 8B-like heads
+        Bv = 256 if B is None else B
+        return make_workload("paper-geometry-b256-w16", L=36 if L is None else L, h_kv=8, h_q=32, d=128, dtype="bf16", b=256,
+                             N_max=9, w=16, B=Bv, N_total=(Bv * 9 + 64 if N_total is None else N_total), seed=seed)
+    raise ValueError("config index must be 0..5")

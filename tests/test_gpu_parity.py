@@ -44,7 +44,8 @@ def test_config0_tiny_fp32_exact():
     (1, dict(B=2, L=2, N_total=300)),      # G=7, w=32, budget 2048
     (2, dict(B=2, L=1, N_total=600)),      # G=4, w=64, budget 4096, per-head keep counts
     (4, dict(B=1, L=1, N_total=600)),      # G=5, w=128, budget 8192
-], ids=["cfg1", "cfg2", "cfg4"])
+    (5, dict(B=2, L=2, N_total=30)),       # the paper's own geometry: block size 256, window 16, budget 2048
+], ids=["cfg1", "cfg2", "cfg4", "paper-geometry"])
 def test_benchmark_shapes_reduced_batch(cfg, kw):
     w = workloads.config(cfg, **kw)
     p, pool, batch = G.workload_problem(w)
