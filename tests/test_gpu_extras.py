@@ -305,3 +305,29 @@ def test_extras_argument_errors():
         with pytest.raises(binding.ZpError) as e:
             c.zp_score_ex(pool, batch, binding.Extras(**bad), s)
         assert e.value.status == binding.ZP_EINVAL
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_refinements_seeded_random_shapes(seed):
+    rng = np.random.default_rng(8000 + seed)
+    Gq = int(rng.choice([1, 2, 4, 5, 8]))
+    b = int(rng.choice([8, 16, 16, 32]))
+    d = int(rng.choice([64, 128]))
+    N_max = int(rng.integers(3, 10))
+    extra = int(rng.integers(0, 3))
+    budget = (N_max - 1) * b
+    w = int(rng.integers(1, min(64, budget) + 1))
+    B, L, h_kv = 2, int(rng.integers(1, 3)), int(rng.integers(1, 3))
+    p = random_problem(8100 + seed, B=B, L=L, h_kv=h_kv, G=Gq, d=d, b=b, N_max=N_max, w=w, extra_blocks=extra, bf16=True, heavy=4)
+    N = N_max + extra
+    vl = rng.integers(max(0, w - b), (N - 1) * b + 1, size=(B, L, h_kv)).astype(np.int32)
+    if seed % 3 == 0:
+        vl[...] = (N - 1) * b
+    p.valid_len = vl
+    cap = np.minimum(budget, vl + b)
+    p.keep = (w + (rng.random(vl.shape) * (cap - w + 1)).astype(np.int32)).clip(w, cap).astype(np.int32)
+    plant_similar_keys(p, rng, 30, noise=0.1)
+    ex = dict(alpha=0.8, use_F=bool(seed % 2 == 0), pool_kernel=int(rng.choice([1, 3, 5])), pool_first_only=bool(seed % 4 == 1))
+    if seed % 3 != 1:
+        ex.update(lam=0.3, tau=0.02, p=pick_threshold(p, [0.4, 0.41, 0.42, 0.43, 0.44]))
+    run_extras_protocol(p, ex, seed=seed)

@@ -161,3 +161,29 @@ def test_workgroup_to_unit_map_does_not_change_results():
         assert torch.equal(a.view(torch.int16) if a.dtype == torch.bfloat16 else a, c.view(torch.int16) if c.dtype == torch.bfloat16 else c)
     rep = G.full_protocol(p, pool, batch)
     assert rep["worst_rel"] < 1e-3
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_seeded_random_shapes(seed):
+    """Shapes, live prefixes and keep counts drawn from a seed: whatever geometry the library picks must pass the protocol."""
+    rng = np.random.default_rng(7000 + seed)
+    Gq = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 16]))
+    b = int(rng.choice([4, 8, 16, 32]))
+    d = int(rng.choice([64, 128]))
+    N_max = int(rng.integers(3, 13))
+    extra = int(rng.integers(0, 4))
+    budget = (N_max - 1) * b
+    w = int(rng.integers(1, min(96, budget) + 1))
+    B, L, h_kv = int(rng.integers(1, 4)), int(rng.integers(1, 3)), int(rng.integers(1, 4))
+    p = random_problem(7100 + seed, B=B, L=L, h_kv=h_kv, G=Gq, d=d, b=b, N_max=N_max, w=w, extra_blocks=extra, bf16=True, heavy=4)
+    N = N_max + extra
+    if seed % 2:
+        vl = rng.integers(max(0, w - b), (N - 1) * b + 1, size=(B, L, h_kv)).astype(np.int32)
+        p.valid_len = vl
+    else:
+        vl = np.full((B, L, h_kv), (N - 1) * b, dtype=np.int32)
+    cap = np.minimum(budget, vl + b)
+    p.keep = (w + (rng.random(vl.shape) * (cap - w + 1)).astype(np.int32)).clip(w, cap).astype(np.int32)
+    pool, batch = G.to_device(p)
+    rep = G.full_protocol(p, pool, batch)
+    assert rep["worst_rel"] < 1e-3
