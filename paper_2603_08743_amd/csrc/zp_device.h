@@ -243,6 +243,11 @@ __device__ inline void select_unit(const Args &a, const Unit &u, unsigned *keys,
 // issued while the previous chunk's stores are still on their way.  One register set: what makes this
 // phase fast is the number of waves per CU that issue memory operations, not the rows a thread holds
 // (a second, alternating set cost registers, i.e. resident waves, and was slower).
+// Moved rows are touched once: they are loaded and stored with the non-temporal hint, so that they do not push the
+// keys of the first sweep, which the second sweep reads again, out of L2 / Infinity Cache (config 2: 15.2 -> 14.7 ms).
+#define ZP_NT_LOAD(p) __builtin_nontemporal_load(p)
+#define ZP_NT_STORE(v, p) __builtin_nontemporal_store(v, p)
+
 template <int U, int FM> struct RowSet {   // FM: 0 K/V only, 1 F read back from global memory, 2 F from the on-chip copy
     u32x4 kk[U], vv[U];
     size_t dof[U];
@@ -265,8 +270,8 @@ __device__ __forceinline__ void rows_load(const Args &a, const Unit &u, const in
             s.dof[i] = row_off(a, u.ls, dst[db], r - db * a.b, u.h) + ch;
             if (so != s.dof[i]) {
                 s.mv[i] = true;
-                s.kk[i] = *(const u32x4 *)(a.k + so);
-                s.vv[i] = *(const u32x4 *)(a.v + so);
+                s.kk[i] = ZP_NT_LOAD((const u32x4 *)(a.k + so));
+                s.vv[i] = ZP_NT_LOAD((const u32x4 *)(a.v + so));
                 if (FM && ch == 0) {                             // one lane per row carries the cached global score
                     s.fdo[i] = f_off(a, u.ls, dst[db], r - db * a.b, u.h);
                     s.fv[i] = FM == 2 ? Sg[t] : a.F[f_off(a, u.ls, tbl[sb], t - sb * a.b, u.h)];
@@ -281,8 +286,8 @@ __device__ __forceinline__ void rows_store(const Args &a, int ch, const RowSet<U
 #pragma unroll
     for (int i = 0; i < U; i++) {
         if (s.mv[i]) {
-            *(u32x4 *)(a.k + s.dof[i]) = s.kk[i];
-            *(u32x4 *)(a.v + s.dof[i]) = s.vv[i];
+            ZP_NT_STORE(s.kk[i], (u32x4 *)(a.k + s.dof[i]));
+            ZP_NT_STORE(s.vv[i], (u32x4 *)(a.v + s.dof[i]));
             if (FM && ch == 0) a.F[s.fdo[i]] = s.fv[i];
         }
     }
