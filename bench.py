@@ -23,7 +23,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # HBM bytes of one launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in
 # profiles/unit_mfma_cfg2_hbm_traffic.md (scaled by the plain-copy calibration); keyed by (config, B, layers per launch)
-MEASURED_TRAFFIC = {(2, 256, 8): 78.43e9}
+MEASURED_TRAFFIC = {(2, 256, 8): 77.32e9}
 
 
 def log(msg):
