@@ -195,7 +195,7 @@ zp_status zp_compress_ex(zp_ctx *ctx, const zp_pool *pool, const zp_batch *batch
 zp_status zp_sync_status(zp_ctx *ctx, void *stream);
 
 /*
- * Check-only helper, NOT part of the compression path and not tuned: paged decode attention over a
+ * Check-only helper, NOT part of the compression path: paged decode attention over a
  * (compacted) cache with per-head lengths, so that a caller can verify that the compacted cache is usable
  * (textbook softmax(q K^T / sqrt d) V; the paper's engine uses its own attention kernels for decoding).
  * pool: k, v and the shape fields are used (q, M, w ignored).  table: [dev] int32 [B][table_stride] logical ->
