@@ -3,7 +3,8 @@
 The oracle cannot run 16 384 units of these shapes, so: (a) a seeded sample of whole requests (every layer of the
 slab, every head) is snapshotted before the launch and checked P1/P2/P3 against the oracle; (b) every unit is checked
 by properties that hold at any size: lengths equal the keep counts, kept lists strictly ascending and ending in the
-window, blocks that belong to no compressing request unchanged, rows beyond k_h of the targets unchanged.
+window, blocks that belong to no compressing request unchanged (rows beyond k_h of the targets are covered by the byte
+comparison of the sampled requests).
 """
 import numpy as np
 import pytest
@@ -82,8 +83,6 @@ def test_full_size_launch(cfg, Ls, n_sample):
     else:
         quiet = torch.from_numpy(np.flatnonzero(~used)).cuda()
     ck_before = (checksum(K, quiet), checksum(V, quiet))
-    # rows beyond k_h of a few target blocks must stay as they were: remember the last target block of sampled requests
-    units = w.B * Ls * w.h_kv
     batch = binding.Batch(block_table=G.dev_i32(w.block_table), num_blocks=G.dev_i32(w.num_blocks), q_slot=G.dev_i32(w.q_slot),
                           N_max=w.N_max, L=w.L, keep=G.dev_i32(w.keep), dst_table=G.dev_i32(dst_table))
     pool = binding.Pool(k=K, v=V, q=Q, layer0=layer0)
