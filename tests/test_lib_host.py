@@ -95,3 +95,12 @@ def test_planner_rejects_bad_input_without_side_effects():
         with pytest.raises(binding.ZpError) as e:
             binding.zp_plan(np.array(tbl, dtype=np.int32), np.array(nb, dtype=np.int32), 4, refcnt, np.array([5], dtype=np.int32))
         assert e.value.status == binding.ZP_EINVAL and np.array_equal(refcnt, before)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it says so and exits before touching a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
