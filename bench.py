@@ -59,7 +59,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=2, help="workload: index into the benchmark configurations (1, 2, 3 or 4); 5 = the paper's own geometry (b=256, w=16)")
     ap.add_argument("--compress-frac", type=float, default=1.0, help="config 3 only: fraction of the 512 requests that compress in this step")
-    ap.add_argument("--slab-layers", type=int, default=8, help="layers per zp_compress launch (layer stride)")
+    ap.add_argument("--slab-layers", type=int, default=0, help="layers per zp_compress launch (layer stride); 0 = as many as fit: the largest "
+                    "divisor of the layer count whose K+V slab stays within 96 GiB (a pristine copy of the slab is kept beside it)")
     ap.add_argument("--batch", type=int, default=None, help="override the number of compressing requests (smaller pool too)")
     ap.add_argument("--cpu-sample-requests", type=int, default=32, help="requests (x one slab of layers) the oracle is timed on; 0 = skip")
     ap.add_argument("--no-check", action="store_true", help="skip comparing the sampled requests with the oracle")
@@ -89,7 +90,11 @@ def main():
     else:   # reduced batch: same per-unit shape, a pool just large enough
         N_max = workloads.config(args.config, B=1, L=1, N_total=2048).N_max
         w = workloads.config(args.config, B=args.batch, N_total=args.batch * N_max + 64)
-    Ls = max(x for x in range(1, min(args.slab_layers, w.L) + 1) if w.L % x == 0)     # largest divisor of L within the request
+    want = args.slab_layers
+    if want <= 0:
+        per_layer = 2 * w.N_total * w.b * w.h_kv * w.d * w.esize
+        want = max(1, int((96 * 2**30) // per_layer))
+    Ls = max(x for x in range(1, min(want, w.L) + 1) if w.L % x == 0)                   # largest divisor of L within the request
     n_slabs = w.L // Ls
     log("workload %s: B=%d L=%d (slabs of %d) h_kv=%d h_q=%d d=%d b=%d N_max=%d w=%d pool=%d blocks" %
         (w.name, w.B, w.L, Ls, w.h_kv, w.h_q, w.d, w.b, w.N_max, w.w, w.N_total))
