@@ -51,8 +51,8 @@
  * Parity pins (tests/, marker "not gpu"): textbook causal softmax attention
  * for G = 1, single softmax row for w = 1, closed-form cases (orthogonal and
  * identical keys), invariants (row sums, range), block-table permutation
- * invariance, brute-force stable-sort selection, the literal two-pointer form
- * of the compaction algorithm, and the block counts of the paper's first
+ * invariance, brute-force stable-sort selection, a sequential in-place
+ * move without a snapshot for the compaction, and the block counts of the paper's first
  * figure (N_max = 4, b = 4, w = 2).  The paper prints no numeric example.
  */
 #include <math.h>

@@ -327,12 +327,6 @@ static hipError_t launch_g(const Args &a, int units, hipStream_t s) {
         hipLaunchKernelGGL((unit_mfma<D, RB, NW, GT, false>), grid, block, a.lds_bytes, s, a);         \
     }                                                                                                  \
     break;
-#ifdef ZP_DEV_FAST   /* development builds: only the instantiation of the 8B-like benchmark shape */
-    switch (a.G) {
-        case 4: ZP_LAUNCH(4)
-        default: return hipErrorInvalidConfiguration;
-    }
-#else
     switch (a.G) {
         case 4: ZP_LAUNCH(4)
         case 5: ZP_LAUNCH(5)
@@ -340,7 +334,6 @@ static hipError_t launch_g(const Args &a, int units, hipStream_t s) {
         case 8: ZP_LAUNCH(8)
         default: ZP_LAUNCH(0)
     }
-#endif
 #undef ZP_LAUNCH
     return hipGetLastError();
 }
@@ -348,10 +341,6 @@ static hipError_t launch_g(const Args &a, int units, hipStream_t s) {
 // the (RB, NW) geometries of one head dimension: WIDE = 0 up to four waves, WIDE = 1 eight waves
 template <int D, int WIDE>
 static hipError_t launch_d(const Args &a, int units, int NW, int RB, hipStream_t s) {
-#ifdef ZP_DEV_FAST
-    if (D == 128 && RB == 1 && NW == 8 && WIDE) return launch_g<D, 1, 8>(a, units, s);
-    return hipErrorInvalidConfiguration;
-#else
     if (!WIDE) {
         if (RB == 1 && NW == 1) return launch_g<D, 1, 1>(a, units, s);
         if (RB == 1 && NW == 2) return launch_g<D, 1, 2>(a, units, s);
@@ -363,7 +352,6 @@ static hipError_t launch_d(const Args &a, int units, int NW, int RB, hipStream_t
         if (RB == 4 && NW == 8) return launch_g<D, 4, 8>(a, units, s);
     }
     return hipErrorInvalidConfiguration;
-#endif
 }
 
 }  // namespace zp

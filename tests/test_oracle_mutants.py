@@ -79,7 +79,7 @@ def pins():
         tc.test_nan_inf_and_negative_zero,
         tc.test_stale_positions_never_kept_and_window_follows_live_sequence,
         lambda: tc.test_matches_stable_argsort_and_dominance(0),
-        lambda: tc.test_gather_form_equals_sequential_two_pointer(0, False),
+        lambda: tc.test_gather_form_equals_in_place_sequential_move(0, False),
         tc.test_logical_content_after_compaction_and_untouched_bytes,
         tc.test_compaction_into_separate_targets_leaves_sources_alone,
         tp.test_first_figure_structure,

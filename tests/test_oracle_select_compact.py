@@ -2,9 +2,9 @@
 
 Selection (Method, "The Compression Process Pipeline": window gets +inf, top-k kept) is
 pinned by a stable argsort, an O(T^2) dominance check and hand-made tie cases.
-Compaction (appendix "KV Cache Compression") is pinned by the literal sequential
-two-pointer form of the paper's algorithm, written here independently of the
-oracle's gather-from-snapshot form, plus whole-pool byte equality and idempotence.
+Compaction (appendix "KV Cache Compression") is pinned by a sequential in-place move
+that keeps no snapshot (the oracle gathers from one), plus whole-pool byte equality
+and idempotence.
 """
 import numpy as np
 import pytest
@@ -114,26 +114,23 @@ def test_full_budget_when_keep_absent():
 
 # ---------------------------------------------------------------- compaction
 
-def two_pointer_compaction(K, V, tbl_src, tbl_dst, tag, l, h, b):
-    """The paper's sequential algorithm, literally: a read pointer walks all N*b slots, a write
-    pointer advances once per kept entry; K and V rows are copied one at a time, in place."""
-    N = len(tbl_src)
-    i = ell = s = 0
-    while i < N:
-        if tag[i][ell % b] == 1:
-            pr = (tbl_src[i], ell % b)
-            pw = (tbl_dst[s // b], s % b)
-            K[l, pw[0], pw[1], h] = K[l, pr[0], pr[1], h]
-            V[l, pw[0], pw[1], h] = V[l, pr[0], pr[1], h]
-            s += 1
-        ell += 1
-        if ell % b == 0:
-            i += 1
-    return s
+def in_place_sequential_move(K, V, tbl_src, tbl_dst, kept_mask, l, h, b):
+    """Order-preserving removal done in place, one row at a time, with no snapshot (appendix "KV Cache Compression"):
+    the kept logical positions are visited in ascending order and the r-th of them lands on logical row r of the
+    targets.  Because it overwrites the pool while it still reads from it, it only agrees with a gather from a
+    snapshot if no row is overwritten before it has been read, which is what the test below establishes."""
+    src_addr = [(tbl_src[t // b], t % b) for t in range(len(tbl_src) * b)]     # logical position -> (physical block, slot)
+    rank = 0
+    for t in np.flatnonzero(kept_mask.reshape(-1)):
+        blk, slot = src_addr[t]
+        K[l, tbl_dst[rank // b], rank % b, h] = K[l, blk, slot, h]
+        V[l, tbl_dst[rank // b], rank % b, h] = V[l, blk, slot, h]
+        rank += 1
+    return rank
 
 
 @pytest.mark.parametrize("seed,bf16", [(0, False), (1, True), (2, False), (3, True)])
-def test_gather_form_equals_sequential_two_pointer(seed, bf16):
+def test_gather_form_equals_in_place_sequential_move(seed, bf16):
     p = random_problem(seed, B=2, L=2, h_kv=2, G=2, d=8, b=4, N_max=4, w=2, bf16=bf16, num_blocks=[6, 4])
     rng = np.random.default_rng(seed)
     p.keep = rng.integers(2, 13, size=(2, 2, 2)).astype(np.int32)
@@ -149,7 +146,7 @@ def test_gather_form_equals_sequential_two_pointer(seed, bf16):
                 tag = np.zeros((N, 4), dtype=np.int8)
                 kept = idx[n, l, h, : ln[n, l, h]]
                 tag[kept // 4, kept % 4] = 1
-                moved = two_pointer_compaction(Kr, Vr, p.block_table[n, :N], p.block_table[n, :3], tag, l, h, 4)
+                moved = in_place_sequential_move(Kr, Vr, p.block_table[n, :N], p.block_table[n, :3], tag, l, h, 4)
                 assert moved == ln[n, l, h] == p.keep[n, l, h]       # the paper's count: k reads and writes
     assert np.array_equal(p.K, Kr) and np.array_equal(p.V, Vr)        # whole pool, stale tails and bystanders included
     assert not np.array_equal(p.K, K0)
