@@ -152,6 +152,22 @@ zp_status zp_compress(zp_ctx *ctx, const zp_pool *pool, const zp_batch *batch, i
                       float *scores_dbg, int32_t *keep_idx_dbg, void *stream);
 
 /*
+ * zp_compress for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Such callers cannot call zp_create (it allocates the status words the kernels report skipped
+ * units through), so this call takes no context: the status words live in a device array that is part of the
+ * library image, 256 bytes on every GPU the library runs on, held until the process ends.  The call allocates and
+ * frees nothing, on the host or on the device, and enqueues kernels only (one small fill kernel that clears the
+ * status words, then the fused kernel).  Its very first call on a device resolves the array's address and loads
+ * the kernels: make that call outside any capture.
+ * Same arguments, results and shape limits as zp_compress(ctx, pool, batch, len_out, NULL, NULL, stream); the
+ * array's size does not grow with the shape, so no shape is refused on its account.  A skipped unit is visible
+ * as len_out = -1 (there is no context to ask); the failure text of a refused call is zp_last_error(NULL).
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two threads)
+ * race on the status words.  Their K/V results and len_out do not depend on those words.
+ */
+zp_status zp_compress_static(const zp_pool *pool, const zp_batch *batch, int32_t *len_out, void *stream);
+
+/*
  * Score refinements layered on the attention score, in the paper's order (appendix "Global Score", "Pooling at
  * the Sequence Dimension", "Lightning Redundancy", "Combining All These Techniques"):
  *   global score   S[t] <- max(alpha * F[t], S[t]) on the live prefix [0, valid_len) of a request that was

@@ -22,7 +22,7 @@ ZP_OPT_SPLIT, ZP_OPT_SPIN_LIMIT, ZP_OPT_STREAMS, ZP_OPT_XCD_MAP = 1, 2, 3, 4
 
 EXPORTS = ("zp_create", "zp_destroy", "zp_last_error", "zp_scratch_bytes", "zp_score", "zp_select_topk", "zp_compact_kv",
            "zp_compress", "zp_sync_status", "zp_validate_batch", "zp_plan", "zp_set_option", "zp_decode_attention", "zp_score_ex",
-           "zp_compact_kv_ex", "zp_compress_ex")
+           "zp_compact_kv_ex", "zp_compress_ex", "zp_compress_static")
 
 
 class ZpError(RuntimeError):
@@ -254,6 +254,18 @@ class Context:
     def zp_scratch_bytes(self, pool: Pool, batch: Batch) -> int:
         p, b = pool.c(), batch.c()
         return int(self.lib.zp_scratch_bytes(ctypes.byref(p), ctypes.byref(b)))
+
+
+def zp_compress_static(pool: Pool, batch: Batch, len_out: torch.Tensor) -> None:
+    """zp_compress without a context and without any allocation (see include/zp.h); asynchronous on the current stream."""
+    lib = load_library()
+    if not torch.cuda.is_available():
+        raise RuntimeError("libzp needs a GPU: no HIP device is visible")
+    p, b = pool.c(), batch.c()
+    assert len_out.is_cuda and len_out.dtype == torch.int32 and len_out.is_contiguous() and len_out.numel() == b.B * p.L_slab * p.h_kv
+    rc = lib.zp_compress_static(ctypes.byref(p), ctypes.byref(b), ctypes.c_void_p(len_out.data_ptr()), _stream())
+    if rc != ZP_OK:
+        raise ZpError(rc, lib.zp_last_error(None).decode())
 
 
 def zp_plan(block_table: np.ndarray, num_blocks: np.ndarray, N_max: int, refcnt: np.ndarray, free_in: np.ndarray):

@@ -8,6 +8,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <unordered_set>
 #include <vector>
@@ -351,6 +352,60 @@ extern "C" zp_status zp_compress(zp_ctx *ctx, const zp_pool *pool, const zp_batc
     a.stages = zp::STAGE_SCORE | zp::STAGE_SELECT | zp::STAGE_COMPACT;
     a.scores_out = scores_dbg; a.keep_idx_out = keep_idx_dbg; a.len_out = len_out;
     return launch(ctx, "zp_compress", a, path, NW, RB, stream);
+}
+
+// ------------------------------------------------------------------ entry point that allocates nothing
+//
+// The unit kernels report a skipped unit through a few status words in device memory.  zp_create allocates them
+// for a context; callers that may not allocate (HIP graph capture, serving loops, harnesses that forbid hipMalloc)
+// cannot create a context, so zp_compress_static keeps those words in a file-scope device array instead.  Every GPU
+// the library runs on holds its own copy of the array at its own address until the process ends.
+#define ZP_STATIC_WORDS 64
+static __device__ __align__(256) int scratch[ZP_STATIC_WORDS];
+
+static const int kMaxDevices = 64;
+static std::mutex g_static_mu;
+static int *g_static_ptr[kMaxDevices];   // device address of `scratch` per device, looked up once (the name itself is only a host-side stand-in)
+
+__global__ void clear_words(int *p, int n) {
+    const int i = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (i < n) p[i] = 0;
+}
+
+extern "C" zp_status zp_compress_static(const zp_pool *pool, const zp_batch *batch, int32_t *len_out, void *stream) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(nullptr, ZP_EHIP, "zp_compress_static: no HIP device (%s)", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(nullptr, ZP_EUNSUPPORTED, "zp_compress_static: device index %d outside [0, %d)", dev, kMaxDevices);
+    int *words = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_static_mu);
+        words = g_static_ptr[dev];
+        if (!words) {                                         // first call on this device, with this device current
+            e = hipGetSymbolAddress((void **)&words, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !words)
+                return fail(nullptr, ZP_EHIP, "zp_compress_static: cannot resolve the status array on device %d (%s)", dev, hipGetErrorString(e));
+            g_static_ptr[dev] = words;
+        }
+    }
+    zp_ctx tmp;                                               // host-side only: carries defaults and the error text
+    tmp.device = dev; tmp.d_status = words; tmp.h_status = nullptr; tmp.scratch = nullptr; tmp.scratch_bytes = 0;
+    tmp.split_mode = -1; tmp.spin_limit = 1 << 21; tmp.max_streams = 8; tmp.xcd_map = 1; tmp.n_cu = 0; tmp.err[0] = 0;
+    zp::Args a; Path path; int NW, RB;
+    zp_status rc = prepare(&tmp, "zp_compress_static", pool, batch, true, &a, &path, &NW, &RB);
+    if (rc == ZP_OK && !len_out && batch->B > 0) rc = fail(&tmp, ZP_EINVAL, "zp_compress_static: len_out is NULL");
+    if (rc == ZP_OK && batch->B > 0) {
+        a.stages = zp::STAGE_SCORE | zp::STAGE_SELECT | zp::STAGE_COMPACT;
+        a.len_out = len_out;
+        // the array keeps the previous call's contents: the flag must start at zero (a fill kernel, not a memset
+        // node, so that the call can be captured in a graph)
+        hipLaunchKernelGGL(clear_words, dim3(1), dim3(64), 0, (hipStream_t)stream, words, 8);
+        e = hipGetLastError();
+        if (e != hipSuccess) rc = fail(&tmp, ZP_EHIP, "zp_compress_static: kernel launch failed: %s", hipGetErrorString(e));
+        else rc = launch(&tmp, "zp_compress_static", a, path, NW, RB, stream);
+    }
+    if (rc != ZP_OK) snprintf(g_err, sizeof(g_err), "%s", tmp.err);
+    return rc;
 }
 
 extern "C" zp_status zp_decode_attention(zp_ctx *ctx, const zp_pool *p, int32_t B, int32_t table_stride, const int32_t *table,
