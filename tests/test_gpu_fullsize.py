@@ -1,10 +1,12 @@
 """Parity at the benchmark's full sizes, in the launch configuration bench.py times (one layer slab per launch).
 
-The oracle cannot run 16 384 units of these shapes, so: (a) a seeded sample of whole requests (every layer of the
-slab, every head) is snapshotted before the launch and checked P1/P2/P3 against the oracle; (b) every unit is checked
-by properties that hold at any size: lengths equal the keep counts, kept lists strictly ascending and ending in the
-window, blocks that belong to no compressing request unchanged (rows beyond k_h of the targets are covered by the byte
-comparison of the sampled requests).
+The oracle cannot score 16 384 units of these shapes, so: (a) a seeded sample of whole requests (every layer of the
+slab, every head; the first and the last request of the batch among them) is snapshotted before the launch and checked
+P1/P2/P3 against the oracle; (b) the selection, which is integer work, is checked on EVERY unit of the launch: the
+oracle's selection on the device's score bits must equal the device's kept lists and lengths; (c) every unit is also
+checked by properties that hold at any size: lengths equal the keep counts, kept lists strictly ascending and ending in
+the window, blocks that belong to no compressing request unchanged (rows beyond k_h of the targets are covered by the
+byte comparison of the sampled requests).
 """
 import numpy as np
 import pytest
@@ -52,10 +54,27 @@ def checksum(t, block_ids, chunk=1024):
     return torch.cat(out) if out else torch.zeros(0, dtype=torch.int64, device=t.device)
 
 
-@pytest.mark.parametrize("cfg,Ls,n_sample", [(1, 28, 2), (2, 8, 2), (4, 8, 1), (3, 8, 2)], ids=["cfg1", "cfg2", "cfg4", "cfg3"])
-def test_full_size_launch(cfg, Ls, n_sample):
+def select_on_every_unit(w, Ls, layer0, scores, keep_idx, ln):
+    """P2 over the whole launch: the oracle's selection on the device's score bits against the device's lists.  The
+    selection reads no key and no table entry, so the oracle gets a one-block dummy pool of the right shape."""
+    dt = np.uint16 if w.dtype == "bf16" else np.float32
+    dummy = oracle.Problem(K=np.zeros((Ls, 1, w.b, w.h_kv, w.d), dtype=dt), V=np.zeros((Ls, 1, w.b, w.h_kv, w.d), dtype=dt),
+                           Q=np.zeros((Ls, 1, w.w, w.h_q, w.d), dtype=dt), block_table=np.where(w.block_table >= 0, 0, -1).astype(np.int32),
+                           num_blocks=w.num_blocks.copy(), q_slot=np.zeros(w.B, dtype=np.int32), N_max=w.N_max,
+                           keep=None if w.keep is None else np.ascontiguousarray(w.keep[:, layer0:layer0 + Ls]))
+    o_idx, o_len = oracle.select(dummy, scores.cpu().numpy())
+    assert np.array_equal(o_len, ln.cpu().numpy()), "P2 (every unit): lengths differ"
+    g_idx = keep_idx.cpu().numpy()
+    bad = np.flatnonzero((o_idx != g_idx).any(axis=-1).reshape(-1))
+    assert bad.size == 0, "P2 (every unit): kept lists differ in %d units, first %d" % (bad.size, bad[0])
+    return o_idx.shape[0] * o_idx.shape[1] * o_idx.shape[2]
+
+
+@pytest.mark.parametrize("cfg,Ls,n_sample,frac", [(1, 28, 8, 1.0), (2, 8, 8, 1.0), (4, 16, 8, 1.0), (3, 8, 8, 0.5), (3, 8, 8, 1.0)],
+                         ids=["cfg1", "cfg2", "cfg4", "cfg3-half", "cfg3-all"])
+def test_full_size_launch(cfg, Ls, n_sample, frac):
     torch.cuda.empty_cache()
-    w = workloads.config(cfg) if cfg != 3 else workloads.config(3, compress_frac=0.5)
+    w = workloads.config(cfg) if cfg != 3 else workloads.config(3, compress_frac=frac)
     layer0 = Ls if w.L > Ls else 0                       # a slab that is not the first one: exercises layer0 offsets
     print("\n%s: B=%d slab layers [%d,%d) pool %d blocks" % (w.name, w.B, layer0, layer0 + Ls, w.N_total), flush=True)
     K, V, Q = w.pools("cuda", layer0, Ls)
@@ -68,11 +87,11 @@ def test_full_size_launch(cfg, Ls, n_sample):
         assert np.array_equal(plan["dst_table"], want["dst_table"]) and np.array_equal(plan["freed"], want["freed"])
         assert np.array_equal(plan["new_table"], want["new_table"]) and np.array_equal(refcnt, want["refcnt"])
     rng = np.random.default_rng(cfg)
-    sample = sorted(rng.choice(w.B, size=n_sample, replace=False).tolist())
-    if cfg == 3:                                          # one sharer and one non-sharer
+    sample = sorted(set([0, w.B - 1] + rng.choice(np.arange(1, w.B - 1), size=n_sample - 2, replace=False).tolist()))
+    if cfg == 3:                                          # sharers and non-sharers among them
         sharers = [n for n in range(w.B) if w.refcnt[w.block_table[n, 0]] > 1]
         loners = [n for n in range(w.B) if w.refcnt[w.block_table[n, 0]] == 1]
-        sample = [sharers[0], loners[0]]
+        sample = sorted(set(sample[:n_sample - 2] + [sharers[0], loners[0]]))
     p, idt = sub_problem(w, K, V, Q, sample, Ls, layer0, dst_table)
     used = np.zeros(w.N_total, dtype=bool)
     used[w.block_table[w.block_table >= 0]] = True
@@ -107,6 +126,9 @@ def test_full_size_launch(cfg, Ls, n_sample):
     ck_after = (checksum(K, quiet), checksum(V, quiet))
     assert torch.equal(ck_before[0], ck_after[0]) and torch.equal(ck_before[1], ck_after[1])
     assert bool(torch.isfinite(scores).all()) and bool((scores >= 0).all())
+    # ---- (b) the selection of every unit against the oracle's, on the device's score bits
+    n_sel = select_on_every_unit(w, Ls, layer0, scores, keep_idx, ln)
+    print("%s: selection equal to the oracle's on all %d units" % (w.name, n_sel), flush=True)
     # ---- (a) sampled requests against the oracle
     st = torch.tensor(sample, device="cuda")
     g_scores = scores[st].cpu().numpy()
