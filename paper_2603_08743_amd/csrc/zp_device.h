@@ -248,53 +248,67 @@ __device__ inline void select_unit(const Args &a, const Unit &u, unsigned *keys,
 #define ZP_NT_LOAD(p) __builtin_nontemporal_load(p)
 #define ZP_NT_STORE(v, p) __builtin_nontemporal_store(v, p)
 
+// A row is addressed by its token index `block * b + slot` inside the unit's (layer, head) plane: one 32-bit multiply-add
+// per row (host-checked to fit), then one 64-bit multiply-add to the byte address.  Sixteen lanes share a row, so this
+// arithmetic is replicated sixteen times per row: it is kept to a dozen instructions.
 template <int U, int FM> struct RowSet {   // FM: 0 K/V only, 1 F read back from global memory, 2 F from the on-chip copy
     u32x4 kk[U], vv[U];
-    size_t dof[U];
+    unsigned dtok[U];
     bool mv[U];
     float fv[FM ? U : 1];
-    unsigned fdo[FM ? U : 1];
 };
 
-template <int U, int FM>
-__device__ __forceinline__ void rows_load(const Args &a, const Unit &u, const int *tbl, const int *dst, const int *list, const float *Sg, int k,
-                                          int r0, int rpp, int rsub, int ch, bool active, RowSet<U, FM> &s) {
+struct RowBase {
+    size_t byte_base;      // byte offset of (layer, block 0, slot 0, head) plus this lane's 16-byte piece
+    unsigned tok_bytes;    // bytes between consecutive tokens
+    unsigned f_base, f_tok;  // the same for the global-score cache, in elements
+};
+
+template <int U, int FM, bool POW2>
+__device__ __forceinline__ void rows_load(const Args &a, const RowBase &rb, const int *tbl, const int *dst, const int *list, const float *Sg, int k,
+                                          int r0, int rpp, int rsub, bool lead, bool active, RowSet<U, FM> &s) {
 #pragma unroll
     for (int i = 0; i < U; i++) {
         const int r = r0 + i * rpp + rsub;
         s.mv[i] = false;
         if (active && r < k) {
             const int t = list[r];
-            const int sb = div_b(a, t), db = div_b(a, r);
-            const size_t so = row_off(a, u.ls, tbl[sb], t - sb * a.b, u.h) + ch;
-            s.dof[i] = row_off(a, u.ls, dst[db], r - db * a.b, u.h) + ch;
-            if (so != s.dof[i]) {
+            unsigned st, dt;
+            if (POW2) {
+                st = ((unsigned)tbl[t >> a.b_shift] << a.b_shift) + (unsigned)(t & (a.b - 1));
+                dt = ((unsigned)dst[r >> a.b_shift] << a.b_shift) + (unsigned)(r & (a.b - 1));
+            } else {
+                const int sb = t / a.b, db = r / a.b;
+                st = (unsigned)tbl[sb] * (unsigned)a.b + (unsigned)(t - sb * a.b);
+                dt = (unsigned)dst[db] * (unsigned)a.b + (unsigned)(r - db * a.b);
+            }
+            s.dtok[i] = dt;
+            if (st != dt) {
                 s.mv[i] = true;
+                const size_t so = rb.byte_base + (size_t)st * rb.tok_bytes;
                 s.kk[i] = ZP_NT_LOAD((const u32x4 *)(a.k + so));
                 s.vv[i] = ZP_NT_LOAD((const u32x4 *)(a.v + so));
-                if (FM && ch == 0) {                             // one lane per row carries the cached global score
-                    s.fdo[i] = f_off(a, u.ls, dst[db], r - db * a.b, u.h);
-                    s.fv[i] = FM == 2 ? Sg[t] : a.F[f_off(a, u.ls, tbl[sb], t - sb * a.b, u.h)];
-                }
+                if (FM && lead) s.fv[i] = FM == 2 ? Sg[t] : a.F[rb.f_base + st * rb.f_tok];   // one lane per row carries the cached global score
             }
         }
     }
 }
 
 template <int U, int FM>
-__device__ __forceinline__ void rows_store(const Args &a, int ch, const RowSet<U, FM> &s) {
+__device__ __forceinline__ void rows_store(const Args &a, const RowBase &rb, bool lead, const RowSet<U, FM> &s) {
 #pragma unroll
     for (int i = 0; i < U; i++) {
         if (s.mv[i]) {
-            ZP_NT_STORE(s.kk[i], (u32x4 *)(a.k + s.dof[i]));
-            ZP_NT_STORE(s.vv[i], (u32x4 *)(a.v + s.dof[i]));
-            if (FM && ch == 0) a.F[s.fdo[i]] = s.fv[i];
+            const size_t dof = rb.byte_base + (size_t)s.dtok[i] * rb.tok_bytes;
+            ZP_NT_STORE(s.kk[i], (u32x4 *)(a.k + dof));
+            ZP_NT_STORE(s.vv[i], (u32x4 *)(a.v + dof));
+            if (FM && lead) a.F[rb.f_base + s.dtok[i] * rb.f_tok] = s.fv[i];
         }
     }
 }
 
-template <int FM>
-__device__ inline void compact_unit(const Args &a, const Unit &u, const int *tbl, const int *dst, const int *list, const float *Sg, int k) {
+template <int FM, bool POW2>
+__device__ __forceinline__ void compact_rows(const Args &a, const Unit &u, const int *tbl, const int *dst, const int *list, const float *Sg, int k) {
     const int tid = threadIdx.x;
     const int cpr = a.row_bytes >> 4;                            // 16-byte pieces per row
     const int rpp = blockDim.x / cpr;                            // rows per pass
@@ -302,14 +316,25 @@ __device__ inline void compact_unit(const Args &a, const Unit &u, const int *tbl
     const bool active = rsub < rpp;
     constexpr int U = ZP_COMPACT_U;
     const int CH = U * rpp;                                      // rows per chunk
+    RowBase rb;
+    rb.tok_bytes = (unsigned)a.h_kv * (unsigned)a.row_bytes;
+    rb.byte_base = ((size_t)u.ls * a.N_total * a.b * a.h_kv + u.h) * (size_t)a.row_bytes + ch;
+    rb.f_tok = (unsigned)a.h_kv;
+    rb.f_base = (unsigned)u.ls * (unsigned)a.N_total * (unsigned)a.b * (unsigned)a.h_kv + (unsigned)u.h;
     RowSet<U, FM> A;
 #pragma unroll 1
     for (int r0 = 0; r0 < k; r0 += CH) {
-        rows_load<U, FM>(a, u, tbl, dst, list, Sg, k, r0, rpp, rsub, ch, active, A);
+        rows_load<U, FM, POW2>(a, rb, tbl, dst, list, Sg, k, r0, rpp, rsub, ch == 0, active, A);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        rows_store<U, FM>(a, ch, A);
+        rows_store<U, FM>(a, rb, ch == 0, A);
     }
+}
+
+template <int FM>
+__device__ inline void compact_unit(const Args &a, const Unit &u, const int *tbl, const int *dst, const int *list, const float *Sg, int k) {
+    if (a.b_shift >= 0) compact_rows<FM, true>(a, u, tbl, dst, list, Sg, k);
+    else compact_rows<FM, false>(a, u, tbl, dst, list, Sg, k);
 }
 
 // ------------------------------------------------------------------ score refinements
