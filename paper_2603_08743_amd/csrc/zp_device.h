@@ -264,9 +264,14 @@ struct RowBase {
     unsigned f_base, f_tok;  // the same for the global-score cache, in elements
 };
 
-template <int U, int FM, bool POW2>
+// KV_APART: a chunk's K rows are all requested before its V rows (small workgroups), instead of K and V row by row.
+// The two pools are separate allocations addressed by the same offsets; which order the memory system prefers depends
+// on how many waves issue the requests (measured: the paper's own geometry with two-wave workgroups runs 41.8-43.3 ms per
+// launch row by row and 35.2-36.8 ms apart; the 8B-like shape with eight-wave workgroups 14.55 ms against 15.16 ms).
+template <int U, int FM, bool POW2, bool KV_APART>
 __device__ __forceinline__ void rows_load(const Args &a, const RowBase &rb, const int *tbl, const int *dst, const int *list, const float *Sg, int k,
                                           int r0, int rpp, int rsub, bool lead, bool active, RowSet<U, FM> &s) {
+    size_t vo[KV_APART ? U : 1];
 #pragma unroll
     for (int i = 0; i < U; i++) {
         const int r = r0 + i * rpp + rsub;
@@ -287,10 +292,16 @@ __device__ __forceinline__ void rows_load(const Args &a, const RowBase &rb, cons
                 s.mv[i] = true;
                 const size_t so = rb.byte_base + (size_t)st * rb.tok_bytes;
                 s.kk[i] = ZP_NT_LOAD((const u32x4 *)(a.k + so));
-                s.vv[i] = ZP_NT_LOAD((const u32x4 *)(a.v + so));
+                if (KV_APART) vo[i] = so;
+                else s.vv[i] = ZP_NT_LOAD((const u32x4 *)(a.v + so));
                 if (FM && lead) s.fv[i] = FM == 2 ? Sg[t] : a.F[rb.f_base + st * rb.f_tok];   // one lane per row carries the cached global score
             }
         }
+    }
+    if (KV_APART) {
+#pragma unroll
+        for (int i = 0; i < U; i++)
+            if (s.mv[i]) s.vv[i] = ZP_NT_LOAD((const u32x4 *)(a.v + vo[KV_APART ? i : 0]));
     }
 }
 
@@ -307,7 +318,7 @@ __device__ __forceinline__ void rows_store(const Args &a, const RowBase &rb, boo
     }
 }
 
-template <int FM, bool POW2>
+template <int FM, bool POW2, bool KV_APART>
 __device__ __forceinline__ void compact_rows(const Args &a, const Unit &u, const int *tbl, const int *dst, const int *list, const float *Sg, int k) {
     const int tid = threadIdx.x;
     const int cpr = a.row_bytes >> 4;                            // 16-byte pieces per row
@@ -324,7 +335,7 @@ __device__ __forceinline__ void compact_rows(const Args &a, const Unit &u, const
     RowSet<U, FM> A;
 #pragma unroll 1
     for (int r0 = 0; r0 < k; r0 += CH) {
-        rows_load<U, FM, POW2>(a, rb, tbl, dst, list, Sg, k, r0, rpp, rsub, ch == 0, active, A);
+        rows_load<U, FM, POW2, KV_APART>(a, rb, tbl, dst, list, Sg, k, r0, rpp, rsub, ch == 0, active, A);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         rows_store<U, FM>(a, rb, ch == 0, A);
@@ -333,8 +344,9 @@ __device__ __forceinline__ void compact_rows(const Args &a, const Unit &u, const
 
 template <int FM>
 __device__ inline void compact_unit(const Args &a, const Unit &u, const int *tbl, const int *dst, const int *list, const float *Sg, int k) {
-    if (a.b_shift >= 0) compact_rows<FM, true>(a, u, tbl, dst, list, Sg, k);
-    else compact_rows<FM, false>(a, u, tbl, dst, list, Sg, k);
+    if (a.b_shift < 0) compact_rows<FM, false, false>(a, u, tbl, dst, list, Sg, k);
+    else if (blockDim.x <= 128) compact_rows<FM, true, true>(a, u, tbl, dst, list, Sg, k);
+    else compact_rows<FM, true, false>(a, u, tbl, dst, list, Sg, k);
 }
 
 // ------------------------------------------------------------------ score refinements
