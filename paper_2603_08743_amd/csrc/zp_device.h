@@ -4,6 +4,8 @@
 #pragma once
 #include "zp_kernels.h"
 
+#include <type_traits>
+
 #ifndef ZP_COMPACT_U
 #define ZP_COMPACT_U 4
 #endif
@@ -533,15 +535,26 @@ __device__ inline void redundancy_mfma(const Args &a, const Unit &u, const int *
 // (rows `rows`, ROWB bytes apart, 16 keys of one block).  K_blk K_blk^T is one 16x16 tile of the matrix cores
 // (v_mfma_f32_16x16x32_bf16, both operands the same fragments: lane L supplies key L%16, elements 8*(L/16).. of every
 // 32-wide step; register i of lane L holds entry (row 4*(L/16) + i, column L%16)).  j_first: live index of the
-// block's first key; rows at or beyond the live prefix are not live.  scratch: 48 words of LDS of this wave.
+// block's first key; rows at or beyond the live prefix are not live.  Everything after the products stays in
+// registers: norms and the column rule travel by lane permutes, the row sums by adds across the 16 lanes of a row group
+// (this step sits inside the tile loop of sweep 2, where every wait on LDS holds up the whole workgroup's barrier).
+// It comes in two parts so that the caller can take the products while the key rows are in LDS and finish later.
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
+// sum over the 16 lanes that share lane/16, the same bits in all of them (a + b and b + a at every step)
+__device__ __forceinline__ float row16_sum(float v) {
+    auto dpp = [](float x, auto ctrl) { return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), decltype(ctrl)::value, 0xF, 0xF, true)); };
+    v += dpp(v, std::integral_constant<int, 0xB1>());      // lane ^ 1 inside every quad
+    v += dpp(v, std::integral_constant<int, 0x4E>());      // lane ^ 2
+    v += dpp(v, std::integral_constant<int, 0x141>());     // mirror inside every half row: the other quad's sum
+    v += dpp(v, std::integral_constant<int, 0x140>());     // mirror inside the row: the other half's sum
+    return v;
+}
+
+// the products: needs the key rows in LDS only here
 template <int D, int ROWB>
-__device__ __forceinline__ void block_row_sums_lds(const Args &a, const Unit &u, const char *rows, int j_first, float inv_len, float *rs,
-                                                   float *scratch, int lane) {
+__device__ __forceinline__ f32x4 block_gram(const char *rows, int lane) {
     const int c = lane & 15, g = lane >> 4;
-    float *inv = scratch, *zv = scratch + 32;
-    int *zr = (int *)(scratch + 16);
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     const char *kp = rows + c * ROWB + g * 16;
 #pragma unroll
@@ -549,47 +562,43 @@ __device__ __forceinline__ void block_row_sums_lds(const Args &a, const Unit &u,
         const bf16x8 f = *(const bf16x8 *)(kp + kk * 64);
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f, f, acc, 0, 0, 0);
     }
-    const bool live_c = j_first + c < u.vl;
-    const int di = c - 4 * g;                                   // register with the diagonal entry, if it is in this lane
-    float dg = 0.f;
+    return acc;
+}
+
+// from the products to the row sums of the block's live keys: rs[j] = (row sum with the column rule applied) / Tv
+__device__ __forceinline__ void block_row_sums(const Args &a, const Unit &u, const f32x4 acc, int j_first, float inv_len, float *rs, int lane) {
+    const int c = lane & 15, g = lane >> 4;
+    // inverse norm of key c from the diagonal entry (c, c), which sits in lane (column c, group c/4), register c%4
+    float dg = acc[0];
 #pragma unroll
-    for (int i = 0; i < 4; i++) dg = i == di ? acc[i] : dg;
-    if (di >= 0 && di < 4) inv[c] = (live_c && dg > 0.f) ? 1.0f / sqrtf(dg) : 0.f;
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");           // LDS serves a wave's accesses in order
-    const float ic = inv[c];
-    float csum = 0.f, lastv = 0.f;
+    for (int i = 1; i < 4; i++) dg = i == (c & 3) ? acc[i] : dg;
+    const float own = (j_first + c < u.vl && dg > 0.f) ? 1.0f / sqrtf(dg) : 0.f;    // meaningful in the diagonal lanes only
+    const float ic = __shfl(own, (c >> 2) * 16 + c);
+    float val[4];
     int last = -1;
 #pragma unroll
     for (int i = 0; i < 4; i++) {
         const int row = 4 * g + i;
-        const float ir = inv[row];
-        float val = 0.f;
-        if (row != c && ir != 0.f && ic != 0.f) val = acc[i] * (ir * ic);
-        csum += val;
-        if (val > a.p_thr) { last = row; lastv = val; }           // rows ascend with i
+        const float ir = __shfl(ic, g * 16 + row);              // the lane of column `row` in this group holds its inverse norm
+        float v = 0.f;
+        if (row != c && ir != 0.f && ic != 0.f) v = acc[i] * (ir * ic);
+        val[i] = v;
+        if (v > a.p_thr) last = row;                            // rows ascend with i
     }
-    // the four lanes of a column (rows 0-3, 4-7, 8-11, 12-15) combine: column sum in row order, last entry above p
-    float s1 = __shfl_xor(csum, 16);
-    float lo = g & 1 ? s1 : csum, hi = g & 1 ? csum : s1;       // (rows of the even group) + (rows of the odd group)
-    const float pair = lo + hi;
-    const float opair = __shfl_xor(pair, 32);
-    const float colsum = g & 2 ? opair + pair : pair + opair;    // same bits in all four lanes
+    // the four lanes of a column (rows 0-3, 4-7, 8-11, 12-15) agree on the last entry above p ...
 #pragma unroll
     for (int off = 16; off <= 32; off <<= 1) {
         const int ol = __shfl_xor(last, off);
-        const float ov = __shfl_xor(lastv, off);
-        if (ol > last) { last = ol; lastv = ov; }
+        last = ol > last ? ol : last;
     }
-    if (g == 0) { zr[c] = last; zv[c] = lastv; }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    if (g == 0 && live_c) {                                      // symmetric: row sum of key c = its column sum, minus what was zeroed in row c
-        float corr = 0.f;
+    // ... it is zeroed where it lives, and every row is summed over the 16 columns
+    float mine = 0.f;
 #pragma unroll
-        for (int cc = 0; cc < 16; cc++)
-            if (zr[cc] == c) corr += zv[cc];
-        rs[j_first + c] = (colsum - corr) * inv_len;
+    for (int i = 0; i < 4; i++) {
+        const float s = row16_sum(4 * g + i == last ? 0.f : val[i]);
+        mine = i == c ? s : mine;
     }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");           // the next block reuses the wave's scratch
+    if (c < 4 && j_first + 4 * g + c < u.vl) rs[j_first + 4 * g + c] = mine * inv_len;
 }
 
 // D > 0: called from the matrix-core kernel for head dimension D (bf16); D = 0: generic kernel, element type DT.

@@ -255,22 +255,41 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ZP
             if (hf == 0) pt[wv * KT + sub * 32 + l32] = ps;
         }
     };
-    // Redundancy (RED, b = 16): a tile holds four blocks of the live prefix; they go to four waves (alternating between
-    // the two halves of an eight-wave workgroup from tile to tile).  The last block, which sits off the 16-grid of the
-    // live sequence, is done in the tail.
+    // Redundancy (RED, b = 16): a tile holds four blocks of the live prefix, one similarity tile each.  Turning a tile
+    // of products into row sums is a chain of dependent lane exchanges which the whole workgroup waits for at the tile
+    // barrier, so it runs once per PAIR of tiles, all eight blocks of the pair on the eight waves at once (fewer waves
+    // take several blocks in turn).  The first tile of a pair is overwritten while the second is worked on, so the
+    // waves that take its blocks compute the products (four registers per block) while it is still theirs to read and
+    // hold them across the barrier.  The last block, off the 16-grid of the live sequence, is done in the tail.
     float *rs_red = (float *)(smem + a.off_R);
     const float inv_len = 1.0f / (float)u.Tv;
-    auto gram_tile = [&](const char *buf, int j0) {
-        constexpr int GRP = NW >= 4 ? NW / 4 : 1, STEP = NW >= 4 ? 4 : NW;
-        if (NW >= 4 && (j0 / KT) % GRP != wv / 4) return;
-        for (int q = wv % 4; q < KT / 16; q += STEP)
-            if (j0 + 16 * q < u.vl)
-                block_row_sums_lds<D, KTl::ROW>(a, u, buf + 16 * q * KTl::ROW, j0 + 16 * q, inv_len, rs_red, rs_red + a.T_max + wv * 96, lane);
+    constexpr int PER = KT / 16, HOLD = (PER + NW - 1) / NW;  // blocks per tile; first-tile blocks one wave takes
+    f32x4 gacc[HOLD];
+    auto gram_first = [&](const char *buf, int j0) {
+#pragma unroll
+        for (int h = 0; h < HOLD; h++) {
+            const int q = wv + h * NW;
+            if (q < PER && j0 + 16 * q < u.vl) gacc[h] = block_gram<D, KTl::ROW>(buf + 16 * q * KTl::ROW, lane);
+        }
+    };
+    // jA: live index of the first tile (products held in gacc); bufB / jB: the second tile, jB < 0 if there is none
+    auto gram_finish = [&](int jA, const char *bufB, int jB) {
+#pragma unroll
+        for (int h = 0; h < HOLD; h++) {
+            const int q = wv + h * NW;
+            if (q < PER && jA + 16 * q < u.vl) block_row_sums(a, u, gacc[h], jA + 16 * q, inv_len, rs_red, lane);
+        }
+        if (jB >= 0) {
+            for (int q = wv; q < 2 * PER; q += NW) {
+                const int qq = q - PER;
+                if (qq >= 0 && jB + 16 * qq < u.vl)
+                    block_row_sums(a, u, block_gram<D, KTl::ROW>(bufB + 16 * qq * KTl::ROW, lane), jB + 16 * qq, inv_len, rs_red, lane);
+            }
+        }
     };
     auto sweep2_tile = [&](const char *buf, float *pt, int j0) {
         if (j0 + KT > u.Tv - w) sweep2_body(buf, pt, j0, std::true_type());
         else sweep2_body(buf, pt, j0, std::false_type());
-        if (RED) gram_tile(buf, j0);
     };
     auto reduce_tile = [&](const float *pt, int j0) {         // fixed-order sum over the waves: deterministic
         if (tid < KT) {
@@ -295,12 +314,17 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ZP
         const int rt = ntiles - 1 - it;
         if (it + 2 < ntiles) gload(rt - 2, stB, ZP_NT2());
         sweep2_tile(buf0, pt0, rt * KT);
+        if (RED) {
+            gram_first(buf0, rt * KT);
+            if (it + 1 >= ntiles) gram_finish(rt * KT, nullptr, -1);
+        }
         if (it + 1 < ntiles) lstore(buf1, stA);
         __syncthreads();
         reduce_tile(pt0, rt * KT);
         if (it + 1 >= ntiles) break;
         if (it + 3 < ntiles) gload(rt - 3, stA, ZP_NT2());
         sweep2_tile(buf1, pt1, (rt - 1) * KT);
+        if (RED) gram_finish(rt * KT, buf1, (rt - 1) * KT);
         if (it + 2 < ntiles) lstore(buf0, stB);
         __syncthreads();
         reduce_tile(pt1, (rt - 1) * KT);
