@@ -332,7 +332,7 @@ def main():
         log("beside decode: compress %.2f -> %.2f ms, decode %.2f -> %.2f ms (serial %.2f ms)" %
             (c_alone, beside["compress_beside_decode_ms"], d_alone, beside["decode_beside_compress_ms"], c_alone + d_alone))
 
-    traffic, traffic_src = (None, None) if (refine or args.config == 3 and args.compress_frac != 1.0) else profiled_traffic(args.config, w.B, Ls)
+    traffic, traffic_src = (None, None) if refine else profiled_traffic(args.config, w.B, Ls)
     out = {
         "metric": "KV tokens compressed/s (score+select+compact)", "value": value, "unit": "KV entries/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
