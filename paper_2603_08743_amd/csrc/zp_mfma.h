@@ -365,7 +365,7 @@ static hipError_t launch_g(const Args &a, int units, hipStream_t s) {
 // the (RB, NW) geometries of one head dimension: WIDE = 0 up to four waves, WIDE = 1 eight waves
 template <int D, int WIDE>
 static hipError_t launch_d(const Args &a, int units, int NW, int RB, hipStream_t s) {
-    if (!WIDE) {
+    if constexpr (!WIDE) {
         if (RB == 1 && NW == 1) return launch_g<D, 1, 1>(a, units, s);
         if (RB == 1 && NW == 2) return launch_g<D, 1, 2>(a, units, s);
         if (RB == 1 && NW == 4) return launch_g<D, 1, 4>(a, units, s);

@@ -3,6 +3,7 @@
     python -m paper_2603_08743_amd.profile_summary traffic --tables T --slab-layers N --fetch DIR --write DIR --name cfg2 --command "..."
     python -m paper_2603_08743_amd.profile_summary sq      --a DIR --b DIR --name cfg2 --command "..."
     python -m paper_2603_08743_amd.profile_summary stats   --csv FILE --bench-log FILE --name cfg2 --command "..."
+    python -m paper_2603_08743_amd.profile_summary resources          (no GPU: compiles the kernels and records the compiler's resource remarks)
 
 `traffic` also records the scaled HBM bytes per launch in profiles/traffic.json together with a hash of the kernel
 sources; bench.py reports that figure as roofline.traffic only while the sources still hash to the same value.
@@ -171,6 +172,43 @@ def cmd_stats(a):
     print("\n".join(md))
 
 
+def cmd_resources(a):
+    """Registers, spills, scratch and occupancy of every kernel instantiation, from hipcc's own remarks."""
+    import re
+    from .build import CSRC, FLAGS
+    files = ["zp_mfma_d128_wide.hip", "zp_mfma_d128.hip", "zp_mfma_d64_wide.hip", "zp_mfma_d64.hip", "zp_kernels.hip", "zp_check.hip"]
+    rows = []
+    from concurrent.futures import ThreadPoolExecutor
+    compile_one = lambda f: subprocess.run(["hipcc", *FLAGS, "--cuda-device-only", "-Rpass-analysis=kernel-resource-usage", "-c", os.path.join(CSRC, f),
+                                            "-o", os.devnull], capture_output=True, text=True)
+    with ThreadPoolExecutor(max_workers=len(files)) as ex:
+        results = list(ex.map(compile_one, files))
+    for f, r in zip(files, results):
+        assert r.returncode == 0, r.stderr[-2000:]
+        for blk in re.split(r"remark: Function Name: ", r.stderr)[1:]:
+            mangled = blk.split()[0]
+            name = subprocess.run(["c++filt", mangled], capture_output=True, text=True).stdout.strip() or mangled
+            v = dict(re.findall(r"remark:\s+([A-Za-z ]+(?:\[[A-Za-z/ ]*\])?): (\S+)", blk))
+            g = lambda k: next((x for kk, x in v.items() if kk.strip().startswith(k)), "?")
+            rows.append((f, short(name), g("VGPRs"), g("AGPRs"), g("VGPRs Spill"), g("SGPRs Spill"), g("ScratchSize"), g("Occupancy")))
+    md = ["# Compiler resource usage of every kernel instantiation (gfx950)", "Command (no GPU needed):",
+          "  python -m paper_2603_08743_amd.profile_summary resources",
+          "  (per source file: hipcc <build flags> --cuda-device-only -Rpass-analysis=kernel-resource-usage -c csrc/<file>)", "",
+          "unit_mfma<D, RB, NW, G, RED>: head dimension, 32-row query blocks per wave, waves per workgroup, group size (0 = run time), RED = redundancy",
+          "taken from the key tiles of sweep 2.  VGPR spills go to scratch memory; SGPR spills go to spare vector-register lanes and cost no memory traffic.", "",
+          "File | kernel | VGPRs | AGPRs | VGPR spills | SGPR spills | scratch bytes/lane | waves/SIMD", "---|---|---|---|---|---|---|---"]
+    md += ["%s | %s | %s | %s | %s | %s | %s | %s" % r for r in rows]
+    used = {"cfg1": "unit_mfma<128, 1, 8, 7, false>", "cfg2 / cfg3": "unit_mfma<128, 1, 8, 4, false>", "cfg2 with redundancy": "unit_mfma<128, 1, 8, 4, true>",
+            "cfg4": "unit_mfma<128, 3, 8, 5, false>", "paper geometry": "unit_mfma<128, 1, 2, 4, false>", "cfg0 (fp32)": "unit_generic<0>"}
+    md += ["", "Instantiations the benchmark workloads run: " + "; ".join("%s: %s" % kv for kv in used.items()) + "."]
+    path = os.path.join(PROFILES, "kernel_resource_usage.md")
+    open(path, "w").write("\n".join(md) + "\n")
+    want = set(used.values())
+    for r in rows:
+        if r[1] in want:
+            print(" | ".join(r))
+
+
 def main():
     ap = argparse.ArgumentParser()
     sub = ap.add_subparsers(dest="what", required=True)
@@ -185,11 +223,12 @@ def main():
     k = sub.add_parser("stats")
     k.add_argument("--csv", required=True)
     k.add_argument("--bench-log", default="")
+    sub.add_parser("resources")
     for p in (t, s, k):
         p.add_argument("--name", required=True)
         p.add_argument("--command", action="append", default=[])
     a = ap.parse_args()
-    {"traffic": cmd_traffic, "sq": cmd_sq, "stats": cmd_stats}[a.what](a)
+    {"traffic": cmd_traffic, "sq": cmd_sq, "stats": cmd_stats, "resources": cmd_resources}[a.what](a)
 
 
 if __name__ == "__main__":
