@@ -64,7 +64,11 @@ __global__ void __launch_bounds__(NW * 64) unit_split(const Args a) {
     const int units = a.B * a.L_slab * a.h_kv;
     int *arrive1 = a.sync + 256, *ready1 = arrive1 + units, *arrive2 = ready1 + units;   // tickets: one 128-byte line per stream
 
-    if (__hip_atomic_load(&a.status[3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) return;   // an earlier wait expired: drain the grid
+    // An earlier wait expired: drain the grid.  One thread reads the flag and the whole workgroup takes the same
+    // exit (a per-thread test could let thread 0 leave before it has drawn the ticket the others then wait for).
+    if (tid == 0) misc->bad = __hip_atomic_load(&a.status[3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (misc->bad) return;
     // logical id in start order
     const int xs = a.NS > 1 ? (int)(blockIdx.x % (unsigned)a.NS) : 0;
     if (tid == 0) misc->sel_digit = atomicAdd(&a.sync[xs * 32], 1);
@@ -353,12 +357,6 @@ static hipError_t launch_g(const Args &a, int units, hipStream_t s) {
         hipLaunchKernelGGL((unit_split<D, RB, NW, GT>), grid, block, a.lds_bytes, s, a);     \
     }                                                                                        \
     break;
-#ifdef ZP_DEV_FAST   /* development builds: only the instantiation of the 8B-like benchmark shape */
-    switch (a.G) {
-        case 4: ZP_LAUNCH(4)
-        default: return hipErrorInvalidConfiguration;
-    }
-#else
     switch (a.G) {
         case 4: ZP_LAUNCH(4)
         case 5: ZP_LAUNCH(5)
@@ -366,17 +364,12 @@ static hipError_t launch_g(const Args &a, int units, hipStream_t s) {
         case 8: ZP_LAUNCH(8)
         default: ZP_LAUNCH(0)
     }
-#endif
 #undef ZP_LAUNCH
     return hipGetLastError();
 }
 
 template <int D>
 static hipError_t launch_d(const Args &a, int units, int NW, int RB, hipStream_t s) {
-#ifdef ZP_DEV_FAST
-    if (D == 128 && RB == 2 && NW == 4) return launch_g<D, 2, 4>(a, units, s);
-    return hipErrorInvalidConfiguration;
-#endif
     if (RB == 1 && NW == 1) return launch_g<D, 1, 1>(a, units, s);
     if (RB == 1 && NW == 2) return launch_g<D, 1, 2>(a, units, s);
     if (RB == 1 && NW == 4) return launch_g<D, 1, 4>(a, units, s);

@@ -28,10 +28,10 @@ TRAFFIC_JSON = os.path.join(PROFILES, "traffic.json")
 
 
 def source_sha() -> str:
-    """Hash of every kernel and API source of the library (the counter driver excluded)."""
+    """Hash of every kernel and API source the library is built from (the counter driver and the unbuilt split kernel excluded)."""
     h = hashlib.sha256()
     for f in sorted(glob.glob(os.path.join(HERE, "csrc", "*"))):
-        if f.endswith((".h", ".hip")) and not f.endswith("zp_prof_driver.hip"):
+        if f.endswith((".h", ".hip")) and not f.endswith("zp_prof_driver.hip") and not os.path.basename(f).startswith("zp_split"):   # what the library is built from
             h.update(os.path.basename(f).encode())
             h.update(open(f, "rb").read())
     return h.hexdigest()[:16]
