@@ -198,17 +198,21 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ZP
     __syncthreads();
 
     // ---------------- sweep 2: S[t] = (1/w) sum_u max_g exp2(x - lse)
-    float lr[RB][16];
+    // The products start from -lse / c instead of zero (the accumulator input of the first matrix instruction), so the
+    // matrix cores deliver x - lse / c, the logit minus the row's normaliser in units of 1 / c: nothing is left to
+    // subtract per logit.  Zero rows have lse = +inf, i.e. start and stay at -inf.
+    f32x16 lrn[RB];
     int ub[RB];                                               // first window row of this half-wave's 16 slots
+    const float inv_c = 1.0f / c;
 #pragma unroll
     for (int rb = 0; rb < RB; rb++) {
         const int gb = wv * RB + rb;
         ub[rb] = (gb * 2 + hf) * UL;
 #pragma unroll
-        for (int i = 0; i < 16; i++) lr[rb][i] = lse[gb * 32 + 4 * hf + 8 * (i >> 2) + (i & 3)];
+        for (int i = 0; i < 16; i++) lrn[rb][i] = -lse[gb * 32 + 4 * hf + 8 * (i >> 2) + (i & 3)] * inv_c;
     }
-    // max_g exp2(x_g - lse_g) = exp2(max_g (x_g - lse_g)): the maximum over the group is taken before the
-    // exponential, so a window row costs one exp2 instead of G.
+    // max_g exp2(x_g - lse_g) = exp2(c max_g (x_g - lse_g) / c): the maximum over the group is taken before the
+    // exponential (c > 0), so a window row costs one multiply and one exp2 instead of G of each.
     auto sweep2_body = [&](const char *buf, float *pt, int j0, auto edge_tag) {
         constexpr bool edge = decltype(edge_tag)::value;
 #pragma unroll
@@ -220,7 +224,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ZP
                 const bf16x8 kf = *(const bf16x8 *)(kp + kk * 32);
 #pragma unroll
                 for (int rb = 0; rb < RB; rb++)
-                    acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][kk], kf, kk ? acc[rb] : zero16, 0, 0, 0);
+                    acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][kk], kf, kk ? acc[rb] : lrn[rb], 0, 0, 0);
             }
             // acc[rb][i]: slot i of this half-wave, key j = j0 + sub*32 + l32
             const int j = j0 + sub * 32 + l32;
@@ -228,9 +232,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ZP
             float ps = 0.f;
 #pragma unroll
             for (int rb = 0; rb < RB; rb++) {
-                float y[16];                                  // x - lse in base 2; zero rows have lse = +inf: y = -inf
-#pragma unroll
-                for (int i = 0; i < 16; i++) y[i] = fmaf(acc[rb][i], c, -lr[rb][i]);
+                const f32x16 &y = acc[rb];                    // (x - lse) / c in base 2; zero rows: -inf
                 if (GT) {
 #pragma unroll
                     for (int ul = 0; ul < (GT ? 16 / GT : 1); ul++) {
@@ -238,7 +240,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ZP
 #pragma unroll
                         for (int g = 1; g < GT; g++) mx = fmaxf(mx, y[ul * GT + g]);
                         if (edge && ub[rb] + ul < thr) mx = -INFINITY;
-                        ps += fexp2(mx);
+                        ps += fexp2(mx * c);
                     }
                 } else {                                      // group size known only at run time
                     float mx = -INFINITY;
@@ -247,7 +249,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ZP
                     for (int i = 0; i < 16; i++) {
                         const float v = (edge && ub[rb] + ul < thr) ? -INFINITY : y[i];
                         mx = fmaxf(mx, v);
-                        if (++g == G) { ps += fexp2(mx); mx = -INFINITY; g = 0; ul++; }
+                        if (++g == G) { ps += fexp2(mx * c); mx = -INFINITY; g = 0; ul++; }
                     }
                 }
             }
