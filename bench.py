@@ -88,8 +88,8 @@ def main():
                     "zp_compress_ex with the paper's recommended settings instead of the plain zp_compress")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (the compression step shards without any exchange; "
-              "see DESIGN.md); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU only (units are independent, so the compression step would shard over "
+              "kv heads or requests without any exchange); --gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

@@ -1,6 +1,6 @@
 """Write the tables of one benchmark workload to a binary file for ``zp_prof_driver``.
 
-    python -m paper_2603_08743_amd.dump_workload --config 2 --out gpurun_out/cfg2.tables [--batch B] [--compress-frac F]
+    python -m paper_2603_08743_amd.dump_workload --config 2 --out /tmp/cfg2.tables [--batch B] [--compress-frac F]
 
 The file holds the shape, the seed, block tables, block counts, query slots, per-head keep counts and, for the
 prefix-sharing workload, the target tables the host planner produces.  The driver regenerates the pool values from the

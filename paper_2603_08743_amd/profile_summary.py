@@ -1,4 +1,4 @@
-"""Turn raw rocprofv3 output (under gpurun_out/) into the short summaries kept under profiles/.
+"""Turn raw rocprofv3 output (a scratch directory of CSV files) into the short summaries kept under profiles/.
 
     python -m paper_2603_08743_amd.profile_summary traffic --tables T --slab-layers N --fetch DIR --write DIR --name cfg2 --command "..."
     python -m paper_2603_08743_amd.profile_summary sq      --a DIR --b DIR --name cfg2 --command "..."
