@@ -202,3 +202,49 @@ def test_global_cache_moves_with_the_kept_entries():
                     t = idx[n, l, h, r]
                     want[l, tbl[r // 4], r % 4, h] = F0[l, tbl[t // 4], t % 4, h]
     assert np.array_equal(F, want) and not np.array_equal(F, F0)
+
+
+def test_redundancy_threshold_at_the_margin_moves_scores_by_a_bounded_amount():
+    """The device takes the `similarity > p` decision in fp32, the oracle in fp64; the GPU cases keep every similarity
+    away from p so that the decision is unique.  What a decision AT the margin can change is bounded.  A similarity value
+    sits at (i, j) and (j, i); when p crosses it, in each of the two columns the entry that is zeroed moves to another
+    entry (or to none), so at most two entries (values <= 1) change in each column: a row sum / Tv moves by at most
+    2 / Tv, the softmax normaliser by a factor within exp(+-2 / (Tv tau)), every entry of R by a factor within
+    exp(+-4 / (Tv tau)), and S - lambda R by at most lambda R (e^{4/(Tv tau)} - 1).  Checked here on the oracle by
+    putting p just below and just above similarities at which a decision does flip.  At the benchmark's size and the
+    recommended settings (Tv = 4112, tau = 0.4) the factor is 1.0024, i.e. a score moves by less than 2.5e-3 lambda R,
+    well inside the 1e-3 (|S| + lambda R) of the GPU comparison whenever lambda R < 0.4 |S|."""
+    b, N = 8, 5
+    p = random_problem(77, B=1, L=1, h_kv=1, G=2, d=6, b=b, N_max=3, w=3, extra_blocks=2)
+    rng = np.random.default_rng(5)
+    tbl = p.block_table[0]
+    for _ in range(6):
+        blk, s1, s2 = tbl[rng.integers(N)], rng.integers(b), rng.integers(b)
+        p.K[0, blk, s2] = p.K[0, blk, s1] + 0.05 * rng.standard_normal(p.K.shape[3:]).astype(np.float32)
+    keys = logical_keys(p, 0, 0, 0)
+    unit = keys / np.linalg.norm(keys, axis=1, keepdims=True)
+    C = unit @ unit.T
+    same_block = np.kron(np.eye(N), np.ones((b, b))) > 0
+    np.fill_diagonal(C, -2.0)
+    cand = np.sort(np.unique(C[same_block & (C > 0.3)]))
+    gaps = np.diff(cand)
+    lam, tau, Tv, eps = 0.3, 0.4, N * b, 1e-9
+    base = oracle.score(p)[0, 0, 0]
+    flips = 0
+    for c_star in cand[1:][gaps > 1e-6]:                               # similarities with clear air below them
+        lo = oracle.score_ex(p, oracle.Extras(lam=lam, tau=tau, p=float(c_star - eps)))[0, 0, 0]
+        hi = oracle.score_ex(p, oracle.Extras(lam=lam, tau=tau, p=float(c_star + eps)))[0, 0, 0]
+        if np.array_equal(lo, hi):                                     # not the last entry above p of its column: nothing flips
+            continue
+        flips += 1
+        check_margin_pair(base, lo, hi, lam, tau, Tv, c_star)
+    assert flips >= 3, "too few thresholds at which a decision flips"
+    # the same bound at the benchmark's size and recommended settings
+    assert np.exp(4.0 / (4112 * 0.4)) - 1.0 < 2.5e-3
+
+
+def check_margin_pair(base, lo, hi, lam, tau, Tv, c_star):
+    R_lo, R_hi = (base - lo) / lam, (base - hi) / lam
+    factor = np.exp(4.0 / (Tv * tau))
+    assert np.all(R_hi <= R_lo * factor * (1 + 1e-12)) and np.all(R_lo <= R_hi * factor * (1 + 1e-12))
+    assert np.abs(hi - lo).max() <= lam * max(R_lo.max(), R_hi.max()) * (factor - 1.0) * (1 + 1e-9)
