@@ -89,23 +89,15 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ZP
     const char *kbase = a.k + ((size_t)u.ls * a.N_total * a.b * a.h_kv + u.h) * (size_t)(D * 2) + (tid - r0 * KTl::CPR) * 16;
     const unsigned tok_bytes = (unsigned)a.h_kv * (D * 2);
     const int gap = (u.N - 1) * a.b - u.vl;                   // stale positions between the live prefix and the last block
-    // Tiles that lie wholly in the live prefix (all but the last one or two) and hold whole blocks need none of the
-    // edge handling: position = live index, the block of a row is the tile's first block plus a per-thread constant
-    // and so is its slot.  One table read, one shift-add and one multiply-add per piece.
-    const bool whole_blocks = a.b_shift >= 0 && a.b <= KT;
-    int cblk[LPT], cslot[LPT];
-#pragma unroll
-    for (int i = 0; i < LPT; i++) {
-        const int r = r0 + i * RSTEP;
-        cblk[i] = whole_blocks ? r >> a.b_shift : 0;
-        cslot[i] = whole_blocks ? r & (a.b - 1) : 0;
-    }
     auto gload = [&](int tile, u32x4 (&st)[LPT], auto nt_tag) {   // rows past the end repeat the last key (masked later)
-        if (whole_blocks && (tile + 1) * KT <= u.vl) {
-            const int *tb = tbl + ((tile * KT) >> a.b_shift);
+        // Tiles that lie wholly in the live prefix (all but the last one or two) need none of the edge handling when
+        // the block size is a power of two: position = live index.  (Eight-wave workgroups only: with fewer waves a
+        // thread loads eight or sixteen pieces per tile and the second copy of that code costs registers.)
+        if (NW == 8 && a.b_shift >= 0 && (tile + 1) * KT <= u.vl) {
 #pragma unroll
             for (int i = 0; i < LPT; i++) {
-                const unsigned tok = ((unsigned)tb[cblk[i]] << a.b_shift) + (unsigned)cslot[i];
+                const int j = tile * KT + i * RSTEP + r0;
+                const unsigned tok = ((unsigned)tbl[j >> a.b_shift] << a.b_shift) + (unsigned)(j & (a.b - 1));
                 if (decltype(nt_tag)::value) st[i] = __builtin_nontemporal_load((const u32x4 *)(kbase + (size_t)tok * tok_bytes));
                 else st[i] = *(const u32x4 *)(kbase + (size_t)tok * tok_bytes);
             }
@@ -326,27 +318,29 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ZP
         }
     };
     float *pt0 = part, *pt1 = part + NW * KT;
-    // tiles are taken in DESCENDING order (tile number rt = ntiles-1-it).  The last two tiles of sweep 1 are still in
-    // LDS (tile t sits in buffer t & 1), so the sweep turns around without waiting for memory; the keys read just before
-    // them are the ones most likely to be still in L2 / Infinity Cache.
-    char *bA = ((ntiles - 1) & 1) ? buf1 : buf0, *bB = ((ntiles - 1) & 1) ? buf0 : buf1;
+    // tiles are taken in DESCENDING order (tile number rt = ntiles-1-it): the keys sweep 1 read last are the ones
+    // most likely to be still in L2 / Infinity Cache
+    gload(ntiles - 1, stA, ZP_NT2());
+    lstore(buf0, stA);
+    if (ntiles > 1) gload(ntiles - 2, stA, ZP_NT2());
+    __syncthreads();
 #pragma unroll 1
     for (int it = 0; it < ntiles; it += 2) {
         const int rt = ntiles - 1 - it;
         if (it + 2 < ntiles) gload(rt - 2, stB, ZP_NT2());
-        sweep2_tile(bA, pt0, rt * KT);
+        sweep2_tile(buf0, pt0, rt * KT);
         if (RED) {
-            gram_first(bA, rt * KT);
+            gram_first(buf0, rt * KT);
             if (it + 1 >= ntiles) gram_finish(rt * KT, nullptr, -1);
         }
-        if (it > 0 && it + 1 < ntiles) lstore(bB, stA);       // the first pair is already there
+        if (it + 1 < ntiles) lstore(buf1, stA);
         __syncthreads();
         reduce_tile(pt0, rt * KT);
         if (it + 1 >= ntiles) break;
         if (it + 3 < ntiles) gload(rt - 3, stA, ZP_NT2());
-        sweep2_tile(bB, pt1, (rt - 1) * KT);
-        if (RED) gram_finish(rt * KT, bB, (rt - 1) * KT);
-        if (it + 2 < ntiles) lstore(bA, stB);
+        sweep2_tile(buf1, pt1, (rt - 1) * KT);
+        if (RED) gram_finish(rt * KT, buf1, (rt - 1) * KT);
+        if (it + 2 < ntiles) lstore(buf0, stB);
         __syncthreads();
         reduce_tile(pt1, (rt - 1) * KT);
     }
