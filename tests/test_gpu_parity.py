@@ -74,6 +74,7 @@ def test_small_random_problems(seed, kw):
     (1, 1, 128, 16, 5, 0), (1, 40, 64, 16, 9, 2), (2, 16, 128, 16, 6, 1), (3, 5, 128, 8, 12, 0), (4, 16, 128, 256, 2, 1),
     (5, 32, 64, 16, 20, 3), (6, 9, 128, 24, 7, 0), (7, 32, 128, 16, 17, 0), (8, 16, 64, 32, 5, 1), (16, 3, 128, 16, 4, 0),
     (4, 200, 128, 16, 30, 0), (8, 128, 64, 16, 12, 0),
+    (4, 64, 128, 128, 3, 1), (8, 32, 64, 64, 4, 0),      # eight-wave workgroups with blocks larger than / equal to a key tile
 ])
 def test_mfma_path_shape_sweep(Gq, w, d, b, N_max, extra):
     p = random_problem(200 + Gq * 7 + w, B=2, L=1, h_kv=2, G=Gq, d=d, b=b, N_max=N_max, w=w, extra_blocks=extra, bf16=True, heavy=4)
