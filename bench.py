@@ -165,18 +165,22 @@ def main():
         if extras is not None and extras.F is not None:
             extras.F.zero_()
 
+    copy_ms = []                                                 # device time of the K+V restore copies (a plain copy of the slab)
+
     def one_step():
         """All slabs of one step; returns the summed device time of the zp_compress launches in ms."""
         evs = []
         for s in range(n_slabs):
+            c0, a, b_ = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+            c0.record()
             restore()
-            a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record()
             compress(pools[s], len_out)
             b_.record()
-            evs.append((a, b_))
+            evs.append((c0, a, b_))
         torch.cuda.synchronize()
-        return [a.elapsed_time(b_) for a, b_ in evs]
+        copy_ms.extend(c0.elapsed_time(a) for c0, a, _ in evs)
+        return [a.elapsed_time(b_) for _, a, b_ in evs]
 
     for _ in range(args.warmup):
         one_step()
@@ -184,6 +188,7 @@ def main():
     torch.cuda.synchronize()
     wall0 = time.time()
     launches = []
+    copy_ms.clear()
     for _ in range(args.steps):
         launches += one_step()
     torch.cuda.synchronize()
@@ -191,6 +196,9 @@ def main():
     ctx.zp_sync_status()
     ms_per_step = sum(launches) / args.steps
     ms_per_launch = sum(launches) / len(launches)
+    # what a plain device copy reaches on this machine: the restore moves the slab's K and V once each way (the library's
+    # kernels are not involved; with refinements the cache clear is in the interval too, so the figure is left out)
+    copy_gbs = None if refine else 2 * 2 * K.numel() * K.element_size() / (sum(copy_ms) / len(copy_ms) * 1e-3) / 1e9
 
     # algorithmic bytes of one launch, from the kept lists of slab 0 (untimed debug run)
     restore()
@@ -215,6 +223,8 @@ def main():
         "(%.1f%% of 2.5 PFLOP/s); moved rows/kept rows = %.3f" %
         (ms_per_step, n_slabs, ms_per_launch, value, achieved, 100 * achieved / HBM_PEAK_GBS, flops_executed / (ms_per_launch * 1e-3) / 1e12,
          100 * flops_executed / (ms_per_launch * 1e-3) / 1e12 / 2500.0, moved / max(1, kept)))
+    if copy_gbs is not None:
+        log("a plain device copy of the slab (the restore between launches) moves %.0f GB/s on this box" % copy_gbs)
 
     cpu = None
     check_failed = False
@@ -345,6 +355,7 @@ def main():
         "request_tokens_per_s": req_tokens_step / (ms_per_step * 1e-3),
         "wall_ms_per_step_incl_restore": wall * 1e3 / args.steps,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "device_copy_GBs_same_run": copy_gbs,
                      "traffic": traffic, "traffic_from": traffic_src, "kernel": "zp::unit_mfma (fused %s)" % ("zp_compress" if extras is None else "zp_compress_ex"), "ms_per_launch": ms_per_launch,
                      "algorithmic_bytes_per_launch": bytes_launch, "moved_rows_per_launch": moved, "kept_rows_per_launch": kept,
                      "mfma": {"algorithmic_tflops": flops_launch / (ms_per_launch * 1e-3) / 1e12, "executed_tflops": flops_executed / (ms_per_launch * 1e-3) / 1e12,
