@@ -104,3 +104,34 @@ def test_bench_refuses_more_than_one_gpu():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_bench_traffic_figure_is_tied_to_the_kernel_sources(tmp_path, monkeypatch):
+    """bench.py quotes the profiled HBM traffic only while the kernel sources hash to what the profile was taken on."""
+    import json
+    import bench
+    from paper_2603_08743_amd import profile_summary
+    sha = profile_summary.source_sha()
+    entry = dict(name="x", config=2, B=256, slab_layers=8, traffic_bytes=123.0, source_sha=sha, summary="profiles/x.md", date="d", head="h")
+    f = tmp_path / "traffic.json"
+    monkeypatch.setattr(profile_summary, "TRAFFIC_JSON", str(f))
+    f.write_text(json.dumps([entry]))
+    value, src = bench.profiled_traffic(2, 256, 8)
+    assert value == 123.0 and src["kernel_sources_unchanged"] is True
+    assert bench.profiled_traffic(2, 128, 8) == (None, None)                 # another launch shape: nothing to quote
+    f.write_text(json.dumps([dict(entry, source_sha="0" * 16)]))            # profile taken on other sources
+    value, src = bench.profiled_traffic(2, 256, 8)
+    assert value is None and src["kernel_sources_unchanged"] is False
+    f.unlink()
+    assert bench.profiled_traffic(2, 256, 8) == (None, None)
+
+
+def test_committed_traffic_profiles_match_the_committed_kernel_sources():
+    """The figures under profiles/ are the ones of the sources in the tree (a kernel change without a new profile fails here)."""
+    import json
+    from paper_2603_08743_amd import profile_summary
+    entries = json.load(open(profile_summary.TRAFFIC_JSON))
+    assert entries, "profiles/traffic.json is empty"
+    sha = profile_summary.source_sha()
+    stale = [e["name"] for e in entries if e["source_sha"] != sha]
+    assert not stale, "profiles taken on other kernel sources: %s" % stale
