@@ -69,3 +69,34 @@ def test_static_entry_point_refuses_bad_arguments_without_launching():
     p, b = pool.c(), batch.c()
     rc = lib.zp_compress_static(ctypes.byref(p), ctypes.byref(b), ctypes.c_void_p(None), ctypes.c_void_p(None))
     assert rc == binding.ZP_EINVAL and b"len_out" in lib.zp_last_error(None)
+
+
+def test_static_entry_point_inside_a_hip_graph():
+    """The callers this entry point is for include code under HIP graph capture: captured after one eager call (which
+    resolves the status array's address), every replay, with eager work and synchronisations in between, must give the
+    eager call's lengths and pool bytes."""
+    w = workloads.config(2, B=2, L=1, N_total=600)
+    _, pool, batch = G.workload_problem(w)
+    units = w.B * w.L * w.h_kv
+    K0, V0 = pool.k.clone(), pool.v.clone()
+    ln_e = torch.full((units,), -7, dtype=torch.int32, device="cuda")
+    binding.zp_compress_static(pool, batch, ln_e)                    # eager
+    torch.cuda.synchronize()
+    Ke, Ve = pool.k.clone(), pool.v.clone()
+    assert (ln_e >= w.w).all() and not torch.equal(bits(Ke), bits(K0))
+    ln_g = torch.full((units,), -7, dtype=torch.int32, device="cuda")
+    pool.k.copy_(K0)
+    pool.v.copy_(V0)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        binding.zp_compress_static(pool, batch, ln_g)
+    for rep in range(3):
+        pool.k.copy_(K0)
+        pool.v.copy_(V0)
+        ln_g.fill_(-7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ln_g, ln_e), "replay %d" % rep
+        assert torch.equal(bits(pool.k), bits(Ke)) and torch.equal(bits(pool.v), bits(Ve)), "replay %d" % rep
