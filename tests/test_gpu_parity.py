@@ -188,3 +188,17 @@ def test_seeded_random_shapes(seed):
     pool, batch = G.to_device(p)
     rep = G.full_protocol(p, pool, batch)
     assert rep["worst_rel"] < 1e-3
+
+
+@pytest.mark.parametrize("w,N_max", [(64, 20), (128, 36)])
+def test_keys_whose_logits_jump_far_above_everything_before_them(w, N_max):
+    """Massive activations: sweep 1 keeps each row's sum of exp2 against a reference that only moves when the sum leaves
+    the safe range, which late keys with logits more than 2^100 above everything before them force; the softmax then is
+    nearly one-hot.  A few keys in later blocks are scaled by 128 (exact in bf16): logits of the order of +-200 in base 2."""
+    p = random_problem(910 + w, B=1, L=1, h_kv=2, G=4 if w == 64 else 5, d=128, b=16, N_max=N_max, w=w, extra_blocks=1, bf16=True, heavy=2)
+    tbl = p.block_table[0]
+    for blk, slot in ((5, 3), (N_max // 2, 9), (N_max - 3, 0), (N_max - 3, 15)):
+        p.K[0, tbl[blk], slot] += np.uint16(7 << 7)                  # exponent + 7: times 128
+    pool, batch = G.to_device(p)
+    rep = G.full_protocol(p, pool, batch)
+    assert rep["worst_rel"] < 1e-3
