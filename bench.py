@@ -72,8 +72,8 @@ def algorithmic_bytes(w, keep_idx, slab_layers, layer0, tbl=None, dst=None):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="workload: index into the benchmark configurations (1, 2, 3 or 4); 5 = the paper's own geometry (b=256, w=16)")
     ap.add_argument("--compress-frac", type=float, default=1.0, help="config 3 only: fraction of the 512 requests that compress in this step")
     ap.add_argument("--slab-layers", type=int, default=0, help="layers per zp_compress launch (layer stride); 0 = as many as fit: the largest "
